@@ -1,0 +1,122 @@
+/*
+ * libtlinattn - TLinFormer's window-over-history attention for AMD MI355X (gfx950).
+ *
+ * The paper (arXiv 2508.20407) builds its linear-cost connectivity out of one primitive,
+ *
+ *     Attention(Q, K, V) = softmax(Q K^T / sqrt(d_k)) V              (Section 3)
+ *
+ * applied with different sources for Q and K/V.  The only terms of its cost model that grow
+ * with the sequence length (Section 4.1, Appendix A: the D*N*W terms) are attentions in which a
+ * bounded window of W query rows attends an N-row history, and every generation-path layer
+ * also runs causal attention inside the window.  This library is exactly those operations:
+ *
+ *   tlin_history_attn        W window queries x N history keys/values, no mask
+ *                            (Focused attention and the first-layer Cross attention, Section 3)
+ *   tlin_window_causal_attn  causal attention inside the window, query i sees keys j <= i
+ *                            (Causal attention / "Internal Cohesion", Section 3)
+ *   tlin_layer_attn          both for the same W rows, combined (Section 3, generation path)
+ *
+ * Conventions common to all entry points
+ *   - All tensor pointers and the workspace are DEVICE pointers owned by the caller.  The
+ *     library never allocates, frees or keeps them.  Inputs are read-only; O must not alias
+ *     an input.  Layout is [B, H, rows, D] with D contiguous; batch/head/row strides are given
+ *     in elements (0 in every slot of a stride triple = dense).
+ *   - Calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and return without synchronising.  Calls using the same workspace must be ordered on
+ *     one stream.
+ *   - Errors are reported by return code only.  Argument validation runs on the host before
+ *     any HIP call, so it behaves the same on a machine without a GPU.
+ *   - Each (b, h) is an independent attention problem; there is no positional term, bias,
+ *     dropout or key/value head sharing.  Non-finite inputs give unspecified outputs.
+ *   - Results are exact softmax attention up to rounding: bf16 inputs are multiplied on the
+ *     matrix cores with fp32 accumulation, softmax weights are rounded to bf16 before the
+ *     second product; fp32 inputs use fp32 arithmetic throughout.
+ */
+#ifndef TLINATTN_H
+#define TLINATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TLIN_OK = 0,
+    TLIN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad stride/alignment/scale */
+    TLIN_ERR_UNSUPPORTED = 2, /* head dimension or dtype combination not implemented */
+    TLIN_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or smaller than required */
+    TLIN_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed */
+} tlin_status;
+
+typedef enum { TLIN_F32 = 0, TLIN_BF16 = 1 } tlin_dtype;
+
+/* How tlin_layer_attn joins the history result and the window result.  The paper only says
+ * the two "are combined" (Section 3); both natural readings are provided.
+ *   SUM   : two independent softmaxes, outputs added.
+ *   JOINT : a single softmax over history keys and causally visible window keys together,
+ *           i.e. rows [N, N+W) of causal attention over the concatenated sequence - the
+ *           connectivity drawn in Figure 2(b). */
+typedef enum { TLIN_COMBINE_SUM = 0, TLIN_COMBINE_JOINT = 1 } tlin_combine;
+
+typedef struct {
+    int32_t B, H;        /* batch, heads: B*H independent problems, each >= 1 */
+    int32_t W;           /* window (query) rows, >= 1 */
+    int32_t N;           /* history rows; >= 1 for tlin_history_attn, >= 0 for tlin_layer_attn,
+                            ignored by tlin_window_causal_attn */
+    int32_t D;           /* head dimension: 64 or 128 */
+    int32_t in_dtype;    /* tlin_dtype of Q, K, V */
+    int32_t out_dtype;   /* tlin_dtype of O */
+    float scale;         /* logit multiplier, finite and > 0; 1/sqrt(D) gives the paper's formula */
+    int32_t num_splits;  /* partitions of the history axis; 0 = choose automatically */
+    int32_t combine;     /* tlin_combine, used by tlin_layer_attn only */
+    /* element strides {batch, head, row}; all three 0 = dense.  Row strides must be >= D and
+     * keep every row 16-byte aligned. */
+    int64_t q_stride[3], kh_stride[3], vh_stride[3], kw_stride[3], vw_stride[3], o_stride[3];
+} tlin_params;
+
+/* Bytes of device workspace sufficient for any of the three calls below with these
+ * parameters (split partials of the history axis plus the window partial).  Pure host
+ * arithmetic.  Returns 0 if the parameters are invalid. */
+size_t tlin_workspace_bytes(const tlin_params *p);
+
+/* Number of history partitions the library will use for these parameters (>= 1), or 0 if the
+ * parameters are invalid.  Pure host arithmetic. */
+int32_t tlin_num_splits(const tlin_params *p);
+
+/* O[b,h,i,:] = sum_j softmax_j(scale * <Q[b,h,i,:], K_hist[b,h,j,:]>) * V_hist[b,h,j,:],
+ * j over all N history rows, no mask (Section 3: Focused / Cross attention; cost D*N*W,
+ * Appendix A).  The history axis is processed in partitions that are merged exactly by
+ * their log-sum-exp statistics.
+ *   Q_win [B,H,W,D], K_hist/V_hist [B,H,N,D] in in_dtype; O [B,H,W,D] in out_dtype.
+ *   lse: nullable, dense fp32 [B,H,W]; receives log(sum_j exp(scale * <q_i, k_j>)).
+ *   ws : workspace of at least tlin_workspace_bytes(p) bytes, 256-byte aligned. */
+tlin_status tlin_history_attn(const tlin_params *p, const void *Q_win, const void *K_hist,
+                              const void *V_hist, void *O, float *lse, void *ws, size_t ws_bytes,
+                              void *stream);
+
+/* Causal attention inside the window: as above with keys K_win/V_win [B,H,W,D] and the
+ * sum restricted to j <= i (Section 3: Causal attention, mask keeps positions j <= i; query
+ * row i is aligned with key row i).  p->N is ignored. */
+tlin_status tlin_window_causal_attn(const tlin_params *p, const void *Q_win, const void *K_win,
+                                    const void *V_win, void *O, float *lse, void *ws,
+                                    size_t ws_bytes, void *stream);
+
+/* One generation-path attention layer (Section 3): history attention and window causal
+ * attention of the same W query rows, joined per p->combine.  With N == 0 (empty history:
+ * the first chunk of the sliding schedule of Section 5.1) both modes return the window
+ * causal attention; K_hist/V_hist may then be NULL. */
+tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void *K_hist,
+                            const void *V_hist, const void *K_win, const void *V_win, void *O,
+                            void *ws, size_t ws_bytes, void *stream);
+
+const char *tlin_status_string(tlin_status s);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t tlin_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TLINATTN_H */

@@ -1,0 +1,23 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_cpu_helpers():
+    """The oracle and the input generator are small C files; build them if absent."""
+    import oracle
+    import tlin_inputs
+    if not os.path.exists(oracle._LIB_PATH):
+        oracle.build()
+    if not os.path.exists(tlin_inputs._LIB_PATH):
+        tlin_inputs.build()
