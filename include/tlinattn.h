@@ -111,6 +111,16 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
                             const void *V_hist, const void *K_win, const void *V_win, void *O,
                             void *ws, size_t ws_bytes, void *stream);
 
+/* Measurement aid (not part of the attention path).  While enabled, every kernel the library
+ * launches is bracketed by a pair of HIP events recorded on the launch stream.
+ * tlin_profile_read waits for the recorded events, returns the summed durations in
+ * milliseconds and the launch counts per kernel class - [0] history partition kernel,
+ * [1] window causal kernel, [2] merge kernel - and clears the record.  The event objects are
+ * created by the library on first use and kept for reuse.  Intended for benchmarks; leave it
+ * off otherwise. */
+tlin_status tlin_profile_enable(int32_t enable);
+tlin_status tlin_profile_read(double ms[3], int64_t launches[3]);
+
 const char *tlin_status_string(tlin_status s);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

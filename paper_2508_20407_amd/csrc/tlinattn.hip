@@ -1,0 +1,407 @@
+// libtlinattn: C-ABI entry points (see include/tlinattn.h), argument validation, partition
+// planning and kernel launches.  gfx950 only.
+#include "tlinattn.h"
+
+#include <math.h>
+
+#include <mutex>
+#include <utility>
+#include <vector>
+
+#include "attn_bf16.h"
+#include "attn_f32.h"
+#include "merge.h"
+
+using namespace tlin;
+
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+
+struct Strides { int64_t b, h, r; };
+
+// Kernel shape chosen for a bf16 problem: NW waves, QB query blocks of 32 rows per wave.
+struct Shape { int nw, qb; int bm() const { return nw * qb * 32; } };
+
+Shape bf16_shape(int W)
+{
+    if (W > 128) return {8, 1};
+    if (W > 64) return {4, 1};
+    return {2, 1};
+}
+
+int key_tile(int in_dtype, int D) { return (in_dtype == TLIN_F32 && D == 128) ? 32 : 64; }
+int query_block(int in_dtype, int W) { return in_dtype == TLIN_F32 ? 32 : bf16_shape(W).bm(); }
+
+// Workgroups the chip holds at once for a given kernel shape (LDS- and register-limited).
+int resident_wgs(int in_dtype, int W)
+{
+    if (in_dtype == TLIN_F32) return kNumCU * 2;
+    const Shape s = bf16_shape(W);
+    return kNumCU * (s.nw >= 8 ? 1 : 2);
+}
+
+// ---- measurement aid: per-kernel timing with HIP events on the launch stream
+enum KernelClass { KC_HISTORY = 0, KC_WINDOW = 1, KC_MERGE = 2, KC_COUNT = 3 };
+
+struct Timed { int cls; hipEvent_t start, stop; };
+struct Profiler {
+    bool on = false;
+    std::vector<Timed> used;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+    std::mutex mu;
+} g_prof;
+
+// Brackets one launch with events when profiling is enabled.
+struct LaunchTimer {
+    bool active = false;
+    Timed t{};
+    hipStream_t st;
+    LaunchTimer(int cls, hipStream_t s) : st(s)
+    {
+        if (!g_prof.on) return;
+        std::lock_guard<std::mutex> lk(g_prof.mu);
+        if (g_prof.pool.empty()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return;
+            if (hipEventCreate(&b) != hipSuccess) { hipEventDestroy(a); return; }
+            g_prof.pool.push_back({a, b});
+        }
+        t = {cls, g_prof.pool.back().first, g_prof.pool.back().second};
+        g_prof.pool.pop_back();
+        active = hipEventRecord(t.start, st) == hipSuccess;
+        if (!active) g_prof.pool.push_back({t.start, t.stop});
+    }
+    ~LaunchTimer()
+    {
+        if (!active) return;
+        hipEventRecord(t.stop, st);
+        std::lock_guard<std::mutex> lk(g_prof.mu);
+        g_prof.used.push_back(t);
+    }
+};
+
+bool dense(const int64_t s[3]) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
+
+Strides resolve(const int64_t s[3], int H, int rows, int D)
+{
+    if (dense(s)) return {(int64_t)H * rows * D, (int64_t)rows * D, (int64_t)D};
+    return {s[0], s[1], s[2]};
+}
+
+tlin_status check_strides(const int64_t s[3], int D, int elem_bytes)
+{
+    if (dense(s)) return TLIN_OK;
+    const int per16 = 16 / elem_bytes;
+    if (s[2] < D || s[0] < 0 || s[1] < 0) return TLIN_ERR_INVALID_ARG;
+    if (s[0] % per16 || s[1] % per16 || s[2] % per16) return TLIN_ERR_INVALID_ARG;
+    return TLIN_OK;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+tlin_status check_common(const tlin_params *p, bool need_history, bool allow_empty_history)
+{
+    if (!p) return TLIN_ERR_INVALID_ARG;
+    if (p->B < 1 || p->H < 1 || p->W < 1) return TLIN_ERR_INVALID_ARG;
+    if ((int64_t)p->B * p->H > (1 << 24)) return TLIN_ERR_INVALID_ARG;
+    if (need_history && (p->N < (allow_empty_history ? 0 : 1))) return TLIN_ERR_INVALID_ARG;
+    if (p->in_dtype != TLIN_F32 && p->in_dtype != TLIN_BF16) return TLIN_ERR_INVALID_ARG;
+    if (p->out_dtype != TLIN_F32 && p->out_dtype != TLIN_BF16) return TLIN_ERR_INVALID_ARG;
+    if (p->D != 64 && p->D != 128) return TLIN_ERR_UNSUPPORTED;
+    if (!(p->scale > 0.f) || !isfinite(p->scale)) return TLIN_ERR_INVALID_ARG;
+    if (p->num_splits < 0) return TLIN_ERR_INVALID_ARG;
+    const int eb = p->in_dtype == TLIN_F32 ? 4 : 2;
+    const int ob = p->out_dtype == TLIN_F32 ? 4 : 2;
+    tlin_status st;
+    if ((st = check_strides(p->q_stride, p->D, eb))) return st;
+    if ((st = check_strides(p->kh_stride, p->D, eb))) return st;
+    if ((st = check_strides(p->vh_stride, p->D, eb))) return st;
+    if ((st = check_strides(p->kw_stride, p->D, eb))) return st;
+    if ((st = check_strides(p->vw_stride, p->D, eb))) return st;
+    if ((st = check_strides(p->o_stride, p->D, ob))) return st;
+    return TLIN_OK;
+}
+
+// Partition plan for the history axis.
+struct Plan { int nsplit, tiles_per_split; };
+
+Plan plan_history(const tlin_params *p)
+{
+    if (p->N < 1) return {0, 0};
+    const int bn = key_tile(p->in_dtype, p->D);
+    const int ntiles = (p->N + bn - 1) / bn;
+    int want;
+    if (p->num_splits > 0) {
+        want = p->num_splits;
+    } else {
+        // Enough workgroups to occupy every compute unit, but at least 4 tiles per partition.
+        const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W) - 1) / query_block(p->in_dtype, p->W));
+        const int64_t target = resident_wgs(p->in_dtype, p->W);
+        want = (int)((target + base - 1) / base);
+        const int cap = ntiles / 4 > 1 ? ntiles / 4 : 1;
+        if (want > cap) want = cap;
+    }
+    if (want < 1) want = 1;
+    if (want > ntiles) want = ntiles;
+    if (want > 1024) want = 1024;
+    const int tps = (ntiles + want - 1) / want;
+    return {(ntiles + tps - 1) / tps, tps};   // no partition is empty
+}
+
+size_t ws_bytes_for(const tlin_params *p, int nparts)
+{
+    const size_t rows = (size_t)p->B * p->H * nparts * p->W;
+    return rows * p->D * sizeof(float) + 2 * rows * sizeof(float);
+}
+
+struct Workspace { float *O, *M, *L; };
+
+Workspace carve(void *ws, const tlin_params *p, int nparts)
+{
+    const size_t rows = (size_t)p->B * p->H * nparts * p->W;
+    float *base = (float *)ws;
+    return {base, base + rows * p->D, base + rows * p->D + rows};
+}
+
+template <int D, int NW, int QB, bool CAUSAL>
+void launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NW, QB, CAUSAL>), dim3(grid), dim3(NW * 64), 0, st, a);
+}
+
+template <int D, bool CAUSAL>
+void launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
+{
+    if (s.nw == 8) launch_bf16_shape<D, 8, 1, CAUSAL>(a, grid, st);
+    else if (s.nw == 4) launch_bf16_shape<D, 4, 1, CAUSAL>(a, grid, st);
+    else launch_bf16_shape<D, 2, 1, CAUSAL>(a, grid, st);
+}
+
+// Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
+tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream_t st)
+{
+    const int qblk = query_block(p->in_dtype, p->W);
+    a.nqb = (p->W + qblk - 1) / qblk;
+    const int64_t grid64 = (int64_t)p->B * p->H * a.nqb * a.nsplit;
+    if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
+    const int grid = (int)grid64;
+    LaunchTimer timer(causal ? KC_WINDOW : KC_HISTORY, st);
+    if (p->in_dtype == TLIN_BF16) {
+        const Shape s = bf16_shape(p->W);
+        if (p->D == 128) causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
+        else causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
+    } else {
+        if (p->D == 128) {
+            if (causal) hipLaunchKernelGGL((attn_f32_kernel<128, true>), dim3(grid), dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((attn_f32_kernel<128, false>), dim3(grid), dim3(256), 0, st, a);
+        } else {
+            if (causal) hipLaunchKernelGGL((attn_f32_kernel<64, true>), dim3(grid), dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((attn_f32_kernel<64, false>), dim3(grid), dim3(256), 0, st, a);
+        }
+    }
+    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+}
+
+tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
+{
+    m.H = p->H;
+    m.W = p->W;
+    m.out_bf16 = p->out_dtype == TLIN_BF16;
+    const int64_t total = (int64_t)p->B * p->H * p->W;
+    if (total > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
+    m.total_rows = (int)total;
+    const int rpb = 256 / (p->D / 4);
+    const int grid = (int)((total + rpb - 1) / rpb);
+    LaunchTimer timer(KC_MERGE, st);
+    if (p->D == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, st, m);
+    else hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, st, m);
+    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+}
+
+AttnArgs base_args(const tlin_params *p, const void *Q, const void *K, const void *V, const int64_t ks[3],
+                   const int64_t vs[3], int nk)
+{
+    AttnArgs a = {};
+    a.Q = Q; a.K = K; a.V = V;
+    const Strides q = resolve(p->q_stride, p->H, p->W, p->D);
+    const Strides k = resolve(ks, p->H, nk, p->D);
+    const Strides v = resolve(vs, p->H, nk, p->D);
+    a.q_sb = q.b; a.q_sh = q.h; a.q_sr = q.r;
+    a.k_sb = k.b; a.k_sh = k.h; a.k_sr = k.r;
+    a.v_sb = v.b; a.v_sh = v.h; a.v_sr = v.r;
+    a.H = p->H; a.W = p->W; a.NK = nk;
+    a.nsplit = 1; a.tiles_per_split = 0x3fffffff;
+    a.scale = p->scale;
+    a.c = p->scale * 1.4426950408889634f;
+    return a;
+}
+
+void set_direct(AttnArgs &a, const tlin_params *p, void *O, float *lse)
+{
+    const Strides o = resolve(p->o_stride, p->H, p->W, p->D);
+    a.direct = 1;
+    a.O = O; a.o_sb = o.b; a.o_sh = o.h; a.o_sr = o.r;
+    a.lse = lse;
+    a.out_bf16 = p->out_dtype == TLIN_BF16;
+}
+
+void set_partial(AttnArgs &a, const Workspace &w, int nparts, int part0)
+{
+    a.direct = 0;
+    a.Opart = w.O; a.Mpart = w.M; a.Lpart = w.L;
+    a.nparts = nparts; a.part0 = part0;
+}
+
+MergeArgs merge_args(const tlin_params *p, const Workspace &w, int nparts, int nhist, bool has_window, bool joint,
+                     void *O, float *lse)
+{
+    MergeArgs m = {};
+    m.Opart = w.O; m.Mpart = w.M; m.Lpart = w.L;
+    m.nparts = nparts; m.nhist = nhist; m.has_window = has_window; m.joint = joint;
+    const Strides o = resolve(p->o_stride, p->H, p->W, p->D);
+    m.O = O; m.o_sb = o.b; m.o_sh = o.h; m.o_sr = o.r;
+    m.lse = lse;
+    return m;
+}
+
+tlin_status check_ws(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return TLIN_OK;
+    if (!ws || !aligned(ws, 256) || have < need) return TLIN_ERR_WORKSPACE;
+    return TLIN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tlin_workspace_bytes(const tlin_params *p)
+{
+    if (check_common(p, true, true) != TLIN_OK) return 0;
+    const Plan pl = plan_history(p);
+    return ws_bytes_for(p, pl.nsplit + 1);
+}
+
+int32_t tlin_num_splits(const tlin_params *p)
+{
+    if (check_common(p, true, false) != TLIN_OK) return 0;
+    return plan_history(p).nsplit;
+}
+
+tlin_status tlin_history_attn(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
+                              void *O, float *lse, void *ws, size_t ws_bytes, void *stream)
+{
+    tlin_status st = check_common(p, true, false);
+    if (st) return st;
+    if (!Q_win || !K_hist || !V_hist || !O) return TLIN_ERR_INVALID_ARG;
+    if (!aligned(Q_win, 16) || !aligned(K_hist, 16) || !aligned(V_hist, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
+    if (lse && !aligned(lse, 4)) return TLIN_ERR_INVALID_ARG;
+    const Plan pl = plan_history(p);
+    hipStream_t hs = (hipStream_t)stream;
+    AttnArgs a = base_args(p, Q_win, K_hist, V_hist, p->kh_stride, p->vh_stride, p->N);
+    a.nsplit = pl.nsplit;
+    a.tiles_per_split = pl.tiles_per_split;
+    if (pl.nsplit == 1) {
+        set_direct(a, p, O, lse);
+        return launch_attn(p, false, a, hs);
+    }
+    if ((st = check_ws(ws, ws_bytes, ws_bytes_for(p, pl.nsplit)))) return st;
+    const Workspace w = carve(ws, p, pl.nsplit);
+    set_partial(a, w, pl.nsplit, 0);
+    if ((st = launch_attn(p, false, a, hs))) return st;
+    return launch_merge(p, merge_args(p, w, pl.nsplit, pl.nsplit, false, true, O, lse), hs);
+}
+
+tlin_status tlin_window_causal_attn(const tlin_params *p, const void *Q_win, const void *K_win, const void *V_win,
+                                    void *O, float *lse, void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    tlin_status st = check_common(p, false, false);
+    if (st) return st;
+    if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
+    if (!aligned(Q_win, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
+    if (lse && !aligned(lse, 4)) return TLIN_ERR_INVALID_ARG;
+    AttnArgs a = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
+    set_direct(a, p, O, lse);
+    return launch_attn(p, true, a, (hipStream_t)stream);
+}
+
+tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
+                            const void *K_win, const void *V_win, void *O, void *ws, size_t ws_bytes, void *stream)
+{
+    tlin_status st = check_common(p, true, true);
+    if (st) return st;
+    if (p->combine != TLIN_COMBINE_SUM && p->combine != TLIN_COMBINE_JOINT) return TLIN_ERR_INVALID_ARG;
+    if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
+    if (p->N > 0 && (!K_hist || !V_hist)) return TLIN_ERR_INVALID_ARG;
+    if (!aligned(Q_win, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
+    if (p->N > 0 && (!aligned(K_hist, 16) || !aligned(V_hist, 16))) return TLIN_ERR_INVALID_ARG;
+    hipStream_t hs = (hipStream_t)stream;
+    if (p->N == 0) {
+        // Empty history: the layer is the window causal attention in both combine modes.
+        AttnArgs a = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
+        set_direct(a, p, O, nullptr);
+        return launch_attn(p, true, a, hs);
+    }
+    const Plan pl = plan_history(p);
+    const int nparts = pl.nsplit + 1;
+    if ((st = check_ws(ws, ws_bytes, ws_bytes_for(p, nparts)))) return st;
+    const Workspace w = carve(ws, p, nparts);
+
+    AttnArgs ah = base_args(p, Q_win, K_hist, V_hist, p->kh_stride, p->vh_stride, p->N);
+    ah.nsplit = pl.nsplit;
+    ah.tiles_per_split = pl.tiles_per_split;
+    set_partial(ah, w, nparts, 0);
+    if ((st = launch_attn(p, false, ah, hs))) return st;
+
+    AttnArgs aw = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
+    set_partial(aw, w, nparts, pl.nsplit);
+    if ((st = launch_attn(p, true, aw, hs))) return st;
+
+    return launch_merge(p, merge_args(p, w, nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr), hs);
+}
+
+tlin_status tlin_profile_enable(int32_t enable)
+{
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.on = enable != 0;
+    return TLIN_OK;
+}
+
+tlin_status tlin_profile_read(double ms[3], int64_t launches[3])
+{
+    if (!ms || !launches) return TLIN_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (int i = 0; i < KC_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+    tlin_status rc = TLIN_OK;
+    for (const Timed &t : g_prof.used) {
+        float e = 0.f;
+        if (hipEventSynchronize(t.stop) != hipSuccess || hipEventElapsedTime(&e, t.start, t.stop) != hipSuccess) {
+            rc = TLIN_ERR_HIP;
+        } else {
+            ms[t.cls] += e;
+            launches[t.cls] += 1;
+        }
+        g_prof.pool.push_back({t.start, t.stop});
+    }
+    g_prof.used.clear();
+    return rc;
+}
+
+const char *tlin_status_string(tlin_status s)
+{
+    switch (s) {
+    case TLIN_OK: return "ok";
+    case TLIN_ERR_INVALID_ARG: return "invalid argument";
+    case TLIN_ERR_UNSUPPORTED: return "unsupported head dimension or dtype";
+    case TLIN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TLIN_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int32_t tlin_version(void) { return kVersion; }
+
+}  // extern "C"

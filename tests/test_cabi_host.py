@@ -1,0 +1,101 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2508_20407_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(b.LIB_PATH), reason="libtlinattn.so not built")
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "tlinattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tlin_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    syms = header_symbols()
+    assert set(syms) == set(b.EXPORTS)
+    L = b.lib()
+    for s in syms:
+        assert getattr(L, s) is not None
+
+
+def test_version_and_status_strings():
+    assert b.version() >= 100
+    seen = {b.status_string(i) for i in range(5)}
+    assert len(seen) == 5 and b.status_string(0) == "ok"
+    assert b.status_string(99) == "unknown status"
+
+
+def test_params_struct_matches_header_layout():
+    # 10 four-byte fields, then six int64[3] arrays aligned to 8
+    assert ctypes.sizeof(b.TlinParams) == 40 + 6 * 24
+    assert b.TlinParams.q_stride.offset == 40 and b.TlinParams.o_stride.offset == 40 + 5 * 24
+
+
+def P(**kw):
+    d = dict(B=1, H=2, W=64, N=1024, D=64, in_dtype=b.TLIN_BF16, out_dtype=b.TLIN_BF16, scale=0.125)
+    d.update(kw)
+    return b.make_params(**d)
+
+
+def test_workspace_and_split_planning_is_pure_host_arithmetic():
+    p = P(B=1, H=32, W=512, N=131072, D=128)
+    s = b.num_splits(p)
+    assert s >= 1
+    need = b.workspace_bytes(p)
+    rows = 32 * (s + 1) * 512
+    assert need == rows * 128 * 4 + 2 * rows * 4
+    assert b.num_splits(P(num_splits=4)) == 4
+    assert b.num_splits(P(num_splits=5)) == 4      # 16 tiles: 4 per partition, none empty
+    assert b.num_splits(P(num_splits=10 ** 6)) == 1024 // 64   # one 64-key tile per partition at most
+    assert b.num_splits(P(N=1)) == 1
+    assert b.workspace_bytes(P(W=0)) == 0 and b.num_splits(P(D=96)) == 0
+
+
+A = 1 << 20   # a fake, suitably aligned device address: validation must fail before it is used
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=0), b.TLIN_ERR_INVALID_ARG), (dict(H=-1), b.TLIN_ERR_INVALID_ARG), (dict(W=0), b.TLIN_ERR_INVALID_ARG),
+    (dict(N=0), b.TLIN_ERR_INVALID_ARG), (dict(D=96), b.TLIN_ERR_UNSUPPORTED), (dict(D=256), b.TLIN_ERR_UNSUPPORTED),
+    (dict(in_dtype=7), b.TLIN_ERR_INVALID_ARG), (dict(out_dtype=-1), b.TLIN_ERR_INVALID_ARG),
+    (dict(scale=0.0), b.TLIN_ERR_INVALID_ARG), (dict(scale=float("nan")), b.TLIN_ERR_INVALID_ARG),
+    (dict(scale=float("inf")), b.TLIN_ERR_INVALID_ARG), (dict(num_splits=-2), b.TLIN_ERR_INVALID_ARG),
+    (dict(q_stride=(64 * 64 * 2, 64 * 64, 60)), b.TLIN_ERR_INVALID_ARG),       # row stride < D
+    (dict(kh_stride=(1024 * 68 * 2, 1024 * 68, 68)), b.TLIN_ERR_INVALID_ARG),  # rows not 16-byte aligned
+])
+def test_history_rejects_bad_params(kw, status):
+    assert b.history_attn_raw(P(**kw), A, A, A, A, None, A, 1 << 30, None) == status
+
+
+def test_null_and_misaligned_pointers_and_workspace():
+    p = P()
+    assert b.num_splits(p) > 1
+    big = 1 << 30
+    assert b.history_attn_raw(p, None, A, A, A, None, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.history_attn_raw(p, A, A, None, A, None, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.history_attn_raw(p, A, A, A, None, None, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.history_attn_raw(p, A + 2, A, A, A, None, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.history_attn_raw(p, A, A, A, A, None, None, 0, None) == b.TLIN_ERR_WORKSPACE
+    assert b.history_attn_raw(p, A, A, A, A, None, A, 16, None) == b.TLIN_ERR_WORKSPACE
+    assert b.history_attn_raw(p, A, A, A, A, None, A + 16, big, None) == b.TLIN_ERR_WORKSPACE
+    assert b.window_causal_attn_raw(p, A, None, A, A, None, None, 0, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.layer_attn_raw(p, A, A, A, A, A, A, None, 0, None) == b.TLIN_ERR_WORKSPACE
+    assert b.layer_attn_raw(p, A, None, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.layer_attn_raw(P(combine=3), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.layer_attn_raw(P(N=-1), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+
+
+def test_binding_fails_loudly_when_library_is_missing(monkeypatch):
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", "/nonexistent/libtlinattn.so")
+    with pytest.raises(ImportError, match="no fallback"):
+        b.lib()

@@ -1,0 +1,173 @@
+"""GPU parity: libtlinattn (through its C-ABI) against the CPU fp64 oracle, element by element,
+on identical seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import tlin_inputs as ti
+import paper_2508_20407_amd as tl
+from helpers import assert_close, sample_rows, to_host64, upload
+
+pytestmark = pytest.mark.gpu
+
+TDT = {ti.F32: torch.float32, ti.BF16: torch.bfloat16}
+
+
+def run_all(w: ti.Workload, rows=None, num_splits=0, check_lse=True, tag=""):
+    """History, window, and both layer modes of one workload against the oracle."""
+    host = ti.make(w)
+    dev = upload(host, w.dtype)
+    Q, Kh, Vh, Kw, Vw = (dev[k] for k in ("Q", "Kh", "Vh", "Kw", "Vw"))
+    sel = (lambda t: t) if rows is None else (lambda t: t[:, :, torch.from_numpy(rows).long().cuda()])
+    name = f"{w.name}{tag}"
+    if w.N > 0:
+        o, lse = tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale, num_splits=num_splits, return_lse=True)
+        ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)
+        assert_close(sel(o), ro, w.dtype, f"{name} history")
+        if check_lse:
+            np.testing.assert_allclose(to_host64(sel(lse.unsqueeze(-1)))[..., 0], rl, rtol=0, atol=2e-4 * max(1.0, np.abs(rl).max()))
+    o, lse = tl.tlin_window_causal_attn(Q, Kw, Vw, scale=w.scale, return_lse=True)
+    ro, rl = oracle.window_causal(host["Q"], host["Kw"], host["Vw"], w.dtype, w.scale, rows)
+    assert_close(sel(o), ro, w.dtype, f"{name} window")
+    if check_lse:
+        np.testing.assert_allclose(to_host64(sel(lse.unsqueeze(-1)))[..., 0], rl, rtol=0, atol=2e-4 * max(1.0, np.abs(rl).max()))
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_layer_attn(Q, Kh if w.N else None, Vh if w.N else None, Kw, Vw, combine=mode, scale=w.scale,
+                               num_splits=num_splits)
+        ro = oracle.layer(host["Q"], host["Kh"] if w.N else None, host["Vh"] if w.N else None, host["Kw"],
+                          host["Vw"], w.dtype, w.scale, omode, rows)
+        assert_close(sel(o), ro, w.dtype, f"{name} layer mode {mode}")
+
+
+# ---------------------------------------------------------------- the fixed workloads
+def test_config1_f32_full():
+    run_all(ti.config(0))
+
+
+def test_config2_bf16_full():
+    run_all(ti.config(1))
+
+
+def test_config3_peaky_reduced_full_compare():
+    # several key tiles and partitions, ragged tail in N, every row compared
+    run_all(ti.shrink(ti.config(2), B=1, H=2, N=4096 + 37))
+
+
+def test_config3_peaky_full_size_sampled_rows():
+    w = ti.config(2)
+    run_all(w, rows=sample_rows(w.W, 4, seed=3))
+
+
+def test_config4_full_size_sampled_rows():
+    w = ti.config(3)
+    run_all(w, rows=sample_rows(w.W, 6, seed=4))
+
+
+@pytest.mark.parametrize("N,W", [(4096, 64), (4096, 512), (16384, 64)])
+def test_sweep_points_sampled_rows(N, W):
+    w = ti.sweep_point(N, W)
+    run_all(w, rows=sample_rows(W, 6, seed=N + W))
+
+
+def test_sweep_largest_point_sampled_rows():
+    w = ti.sweep_point(262144, 64)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = upload(host, w.dtype)
+    rows = sample_rows(w.W, 2, seed=9)
+    o = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale)
+    ro, _ = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)
+    assert_close(o[:, :, torch.from_numpy(rows).long().cuda()], ro, w.dtype, w.name)
+
+
+def test_degenerate_empty_history_is_standard_causal_attention():
+    """N_hist = 0, W = 4096: the layer, in both modes, is plain causal attention of length W."""
+    w = ti.degenerate_causal()
+    host = ti.make(w, which=("Q", "Kw", "Vw"))
+    dev = upload(host, w.dtype)
+    rows = sample_rows(w.W, 48, seed=5)
+    ro, _ = oracle.window_causal(host["Q"], host["Kw"], host["Vw"], w.dtype, w.scale, rows)
+    idx = torch.from_numpy(rows).long().cuda()
+    o_win = tl.tlin_window_causal_attn(dev["Q"], dev["Kw"], dev["Vw"], scale=w.scale)
+    assert_close(o_win[:, :, idx], ro, w.dtype, "window W=4096")
+    for mode in (tl.TLIN_COMBINE_SUM, tl.TLIN_COMBINE_JOINT):
+        o = tl.tlin_layer_attn(dev["Q"], None, None, dev["Kw"], dev["Vw"], combine=mode, scale=w.scale)
+        assert torch.equal(o, o_win)
+
+
+# ---------------------------------------------------------------- shapes, tails, degenerate cases
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("W,N", [(1, 1), (1, 200), (31, 63), (33, 65), (64, 64), (100, 1000), (129, 129),
+                                 (257, 300), (300, 2049)])
+def test_ragged_shapes(dtype, D, W, N):
+    w = ti.Workload(f"ragged_{dtype}_{D}_{W}_{N}", 1, 2, D, N, W, dtype, 1.0, 77 + W * 131 + N)
+    run_all(w)
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+def test_split_count_invariance_and_determinism(dtype):
+    w = ti.Workload(f"splits_{dtype}", 1, 2, 128, 3000, 96, dtype, 1.0, 4242)
+    host = ti.make(w)
+    dev = upload(host, w.dtype)
+    ro, _ = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    outs = []
+    for s in (1, 2, 3, 7, 47, 1000):
+        o = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, num_splits=s, out_dtype=torch.float32)
+        assert_close(o, ro, w.dtype, f"num_splits={s}")
+        o2 = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, num_splits=s, out_dtype=torch.float32)
+        assert torch.equal(o, o2), "run-to-run results differ"
+        outs.append(to_host64(o))
+    for o in outs[1:]:
+        assert np.abs(o - outs[0]).max() <= (1e-5 if dtype == ti.F32 else 5e-3)
+
+
+def test_strided_views_and_f32_output_for_bf16_inputs():
+    w = ti.Workload("strided", 2, 3, 128, 500, 70, ti.BF16, 1.0, 999)
+    host = ti.make(w)
+    dev = upload(host, w.dtype)
+    # [B, rows, H, D] storage viewed as [B, H, rows, D]: head stride D, row stride H*D
+    def interleave(t):
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Q, Kh, Vh, Kw, Vw = (interleave(dev[k]) for k in ("Q", "Kh", "Vh", "Kw", "Vw"))
+    assert not Q.is_contiguous()
+    o = tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=tl.TLIN_COMBINE_JOINT, scale=w.scale, out_dtype=torch.float32)
+    ro = oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.JOINT)
+    assert o.dtype == torch.float32
+    assert_close(o, ro, w.dtype, "strided joint")
+    o = tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale)
+    ro, _ = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    assert_close(o, ro, w.dtype, "strided history")
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+def test_invariants_hold_on_the_gpu_result(dtype):
+    w = ti.Workload(f"inv_{dtype}", 1, 2, 64, 777, 50, dtype, 1.0, 31337)
+    dev = upload(ti.make(w), w.dtype)
+    Q, Kh, Vh, Kw, Vw = (dev[k] for k in ("Q", "Kh", "Vh", "Kw", "Vw"))
+    ones_h, ones_w = torch.ones_like(Vh), torch.ones_like(Vw)
+    tol = 1e-5 if dtype == ti.F32 else 8e-3
+    o = tl.tlin_history_attn(Q, Kh, ones_h, scale=w.scale, out_dtype=torch.float32)
+    assert (o - 1).abs().max().item() <= tol          # rows are convex combinations
+    o = tl.tlin_layer_attn(Q, Kh, ones_h, Kw, ones_w, combine=tl.TLIN_COMBINE_SUM, scale=w.scale, out_dtype=torch.float32)
+    assert (o - 2).abs().max().item() <= 2 * tol
+    o = tl.tlin_layer_attn(Q, Kh, ones_h, Kw, ones_w, combine=tl.TLIN_COMBINE_JOINT, scale=w.scale, out_dtype=torch.float32)
+    assert (o - 1).abs().max().item() <= tol
+    # history is a set: a joint permutation of its rows changes nothing beyond rounding
+    perm = torch.randperm(w.N, generator=torch.Generator().manual_seed(1)).cuda()
+    o1 = tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale, out_dtype=torch.float32)
+    o2 = tl.tlin_history_attn(Q, Kh[:, :, perm].contiguous(), Vh[:, :, perm].contiguous(), scale=w.scale, out_dtype=torch.float32)
+    assert (o1 - o2).abs().max().item() <= (2e-6 if dtype == ti.F32 else 1e-2)
+    # causal row 0 is the first value row
+    o = tl.tlin_window_causal_attn(Q, Kw, Vw, scale=w.scale)
+    assert torch.equal(o[:, :, 0], Vw[:, :, 0])
+
+
+def test_errors_are_reported_not_raised_by_the_gpu():
+    w = ti.Workload("err", 1, 1, 64, 128, 16, ti.BF16, 1.0, 5)
+    dev = upload(ti.make(w), w.dtype)
+    with pytest.raises(tl.TlinError) as e:
+        tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=-1.0)
+    assert e.value.status == tl.binding.TLIN_ERR_INVALID_ARG
+    with pytest.raises(ValueError):
+        tl.tlin_history_attn(dev["Q"].cpu(), dev["Kh"], dev["Vh"])
