@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of libtlinattn on one MI355X.
+
+A step is one pass of the whole attention path over one batch of synthetic input:
+tlin_layer_attn = history attention over all N rows (split into partitions), causal attention
+inside the window, and the merge that joins them.  Inputs are generated on the host from a
+seed, uploaded once and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is TFLOP/s of the step (4*B*H*W*N*D history flops plus the
+causal half of the window); tokens/s and the fraction of the bf16 MFMA peak are given beside
+it.  `roofline` is for the dominant kernel (the history partition kernel), timed with HIP
+events on the launch stream inside this run; `cpu_baseline` is the fp64 oracle timed on the
+host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+PEAK_F32_VALU_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="1..4: the fixed workloads (default 4: N=131072, W=512, bf16)")
+    ap.add_argument("--combine", choices=("sum", "joint"), default="sum")
+    ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--sweep", action="store_true", help="latency-vs-N sweep instead of the single workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
+    return ap.parse_args()
+
+
+def upload(host, dtype, ti, torch, np):
+    dev = {}
+    for k, a in host.items():
+        dev[k] = (torch.from_numpy(a).cuda() if dtype == ti.F32
+                  else torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16))
+    return dev
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(w, host, target_s, oracle, np):
+    """Oracle layer (SUM: one history softmax plus one window softmax per row) on a seeded row
+    sample sized for about target_s seconds; returns the JSON object."""
+    rng = np.random.default_rng(12345)
+    probe = np.sort(rng.choice(w.W, size=min(w.W, 1), replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM, probe)
+    t_probe = time.perf_counter() - t0            # B*H rows in parallel over the cores
+    rows_per_head = int(max(1, min(w.W, target_s / max(t_probe, 1e-4) * len(probe))))
+    rows = np.sort(rng.choice(w.W, size=rows_per_head, replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM, rows)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * w.B * w.H * w.D * (len(rows) * w.N + float(np.sum(rows + 1)))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{len(rows)} of {w.W} window rows in each of {w.B * w.H} heads, full history, fp64, "
+                      f"{dt:.1f} s",
+            "window_tokens_per_s": w.B * len(rows) / dt * (1.0),
+            "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (every (batch, head) problem is independent; "
+              "no multi-GPU path exists). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import tlin_inputs as ti
+    import paper_2508_20407_amd as tl
+    from paper_2508_20407_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    combine = tl.TLIN_COMBINE_SUM if args.combine == "sum" else tl.TLIN_COMBINE_JOINT
+
+    if args.sweep:
+        return sweep(args, ti, tl, binding, torch, np, combine)
+
+    w = ti.config(args.config - 1)
+    host = ti.make(w)
+    dev = upload(host, w.dtype, ti, torch, np)
+    Q, Kh, Vh, Kw, Vw = (dev[k] for k in ("Q", "Kh", "Vh", "Kw", "Vw"))
+    ws = tl.Workspace()
+
+    def step():
+        return tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=combine, scale=w.scale, num_splits=args.num_splits,
+                                  workspace=ws)
+
+    sec = time_steps(step, args.steps, args.warmup, torch)
+
+    # Per-kernel durations: the same K steps again with event pairs around every launch.
+    binding.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms, launches = binding.profile_read()
+    binding.profile_enable(False)
+    hist_ms = ms[0] / max(launches[0], 1)
+    win_ms = ms[1] / max(launches[1], 1)
+    merge_ms = ms[2] / max(launches[2], 1)
+
+    flops_h, flops_w = w.flops_history(), w.flops_window()
+    tflops = (flops_h + flops_w) / sec / 1e12
+    esz = 4 if w.dtype == ti.F32 else 2
+    kv_bytes = 2.0 * w.B * w.H * w.N * w.D * esz              # K_hist + V_hist, each read once
+    hist_tflops = flops_h / (hist_ms * 1e-3) / 1e12
+    hist_gbs = kv_bytes / (hist_ms * 1e-3) / 1e9
+    # Arithmetic intensity of the history kernel is W flop/byte (bf16): it is matrix-core bound
+    # when W exceeds the ridge point peak_flops/peak_bw, else HBM bound.  fp32 inputs use the
+    # vector ALUs.
+    if w.dtype == ti.F32:
+        roof = {"bound": "alu", "achieved": hist_tflops, "peak": PEAK_F32_VALU_TFLOPS, "unit": "TFLOP/s"}
+    elif w.W >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        roof = {"bound": "mfma", "achieved": hist_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": hist_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = "attn_bf16_kernel (history partitions)" if w.dtype == ti.BF16 else "attn_f32_kernel (history partitions)"
+    roof["kernel_ms"] = hist_ms
+    roof["traffic"] = measured_traffic(w.name)
+
+    out = {
+        "metric": "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == ti.F32 else "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "D": w.D, "N_history": w.N, "W_window": w.W,
+                   "combine": args.combine, "num_splits": binding.num_splits(tl.params_for(Q, w.N, num_splits=args.num_splits)),
+                   "step": "tlin_layer_attn = history partitions + window causal + merge"},
+        "window_tokens_per_s": w.B * w.W / sec, "context_tokens_per_s": w.B * w.N / sec,
+        "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_MFMA_TFLOPS,
+        "kernels_ms": {"history": hist_ms, "window_causal": win_ms, "merge": merge_ms},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np)
+    print(json.dumps(out), flush=True)
+
+
+def measured_traffic(name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
+    (profiles/hbm_traffic.json), or None when no measurement exists for this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name, {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def sweep(args, ti, tl, binding, torch, np, combine):
+    """Latency of tlin_history_attn vs N at fixed W, with a least-squares line per W (the cost
+    model of Section 4.1 predicts exact linearity in N)."""
+    pts = ti.sweep_points()
+    ws = tl.Workspace()
+    results = []
+    for w in pts:
+        host = ti.make(w, which=("Q", "Kh", "Vh"))
+        dev = upload(host, w.dtype, ti, torch, np)
+        Q, Kh, Vh = dev["Q"], dev["Kh"], dev["Vh"]
+        sec = time_steps(lambda: tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale, workspace=ws), args.steps, args.warmup, torch)
+        tf = w.flops_history() / sec / 1e12
+        gbs = 2.0 * w.B * w.H * w.N * w.D * 2 / sec / 1e9
+        results.append({"N": w.N, "W": w.W, "ms": sec * 1e3, "TFLOP/s": tf, "GB/s": gbs,
+                        "pct_mfma_peak": 100 * tf / PEAK_BF16_MFMA_TFLOPS, "pct_hbm_peak": 100 * gbs / PEAK_HBM_GBS})
+        print(json.dumps(results[-1]), file=sys.stderr, flush=True)
+        del dev, Q, Kh, Vh, host
+        torch.cuda.empty_cache()
+    fits = {}
+    for W in sorted({r["W"] for r in results}):
+        xs = np.array([r["N"] for r in results if r["W"] == W], dtype=np.float64)
+        ys = np.array([r["ms"] for r in results if r["W"] == W], dtype=np.float64)
+        a, b = np.polyfit(xs, ys, 1)
+        pred = a * xs + b
+        r2 = 1.0 - float(((ys - pred) ** 2).sum() / ((ys - ys.mean()) ** 2).sum())
+        fits[str(W)] = {"ms_per_history_row": a, "intercept_ms": b, "r2": r2}
+    wd = ti.degenerate_causal()
+    host = ti.make(wd, which=("Q", "Kw", "Vw"))
+    dev = upload(host, wd.dtype, ti, torch, np)
+    sec = time_steps(lambda: tl.tlin_layer_attn(dev["Q"], None, None, dev["Kw"], dev["Vw"], combine=combine, scale=wd.scale),
+                     args.steps, args.warmup, torch)
+    degenerate = {"N": 0, "W": wd.W, "ms": sec * 1e3, "TFLOP/s": wd.flops_window() / sec / 1e12}
+    print(json.dumps({"metric": "latency vs N sweep (tlin_history_attn, bf16, B=1, H=32, D=128)", "points": results,
+                      "linear_fit": fits, "empty_history_causal": degenerate, "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "data": "synthetic"}), flush=True)
+
+
+if __name__ == "__main__":
+    main()
