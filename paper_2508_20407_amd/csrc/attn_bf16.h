@@ -19,10 +19,21 @@
 //   * V is stored row-major [key][d]; the A operand needs 4 consecutive keys at fixed d per
 //     lane, which is what ds_read_b64_tr_b16 returns (16 lanes read a 4x16 patch and get its
 //     transpose).  Two such reads form one 8-element operand.
-//   * K/V tiles of 64 keys go HBM -> registers -> LDS with 16-byte accesses, double buffered,
-//     one barrier per tile; the next tile's global loads are in flight during compute.
+//   * K/V tiles of 64 keys go HBM -> LDS directly (global_load_lds_dwordx4: each wave
+//     instruction moves 1 KB, lane i landing at base + 16*i) through a ring of NSTAGE tiles,
+//     with the loads of the next NSTAGE-1 tiles in flight during compute: one workgroup per CU
+//     has to keep ~100 KB outstanding to cover HBM latency at full bandwidth.  One barrier per
+//     tile; completion is tracked by hand with s_waitcnt vmcnt.
+//   * Ping-pong (PP): with two waves per SIMD, the upper half of the waves runs half a tile out
+//     of phase - in the interval after barrier t it first finishes tile t-1 (value product)
+//     and then does scores and softmax of tile t, while the lower half does scores, softmax
+//     and value product of tile t.  The SIMD then has one wave in a matrix-core phase while
+//     the other is in its softmax (vector ALU) phase, instead of both alternating in lockstep.
+//     V tiles live one interval longer, so the prefetch distance is one tile shorter.
 //   * LDS rows are XOR-swizzled at 16-byte-chunk granularity so that the ds_read_b128 of the
-//     K operand and the transposed reads of V are bank-conflict free on the 64-bank LDS.
+//     K operand and the transposed reads of V are bank-conflict free on the 64-bank LDS.  The
+//     direct loads write LDS linearly, so the swizzle is applied on the source side: the lane
+//     that lands on chunk position c of row r fetches chunk c ^ swz(r) of that row.
 #pragma once
 #include "common.h"
 
@@ -41,27 +52,56 @@ template <> struct Swz<64> {    // 128-byte rows, 8 chunks; two rows per 256-byt
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-template <int D, int NW, int QB, bool CAUSAL>
+// One wave-wide direct load: 64 lanes x 16 bytes from per-lane global addresses to the 1 KB of
+// LDS starting at the wave-uniform byte offset lds_base (lane i lands at lds_base + 16*i).
+// Issued through inline assembly on purpose: the compiler then does not know that LDS is
+// being written asynchronously and does not put a wait-for-all-loads in front of every LDS
+// read; completion is tracked explicitly with wait_vmcnt() before the tile's barrier.
+__device__ __forceinline__ void direct_load_1k(const char *gsrc, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(gsrc)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ unsigned lds_offset(const char *p)
+{
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int D, int NW, int QB, bool CAUSAL, bool PP, int NSTAGE>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 {
     constexpr int BN = 64;                 // keys per tile
     constexpr int BM = NW * QB * 32;       // query rows per workgroup
-    constexpr int NT = NW * 64;
     constexpr int ROWB = D * 2;            // bytes per K/V row
     constexpr int TILE_B = BN * ROWB;
     constexpr int CPR = ROWB / 16;         // 16-byte chunks per row
-    constexpr int CHUNKS = BN * CPR;
-    constexpr int LPT = CHUNKS / NT;       // chunks per thread per tensor per tile
-    static_assert(CHUNKS % NT == 0 && LPT >= 1, "tile does not divide over the workgroup");
+    constexpr int RPI = 1024 / ROWB;       // rows moved by one wave-wide direct load
+    constexpr int NDMA = BN / RPI / NW;    // direct loads per wave per tensor per tile
+    static_assert(BN % (RPI * NW) == 0 && NDMA >= 1, "tile does not divide over the waves");
+    static_assert(!PP || NW % 2 == 0, "ping-pong needs an even number of waves");
     constexpr int DS = D / 16;             // contraction steps of Q K^T
     constexpr int DB = D / 32;             // 32-row blocks of O^T
+    constexpr int PD = PP ? NSTAGE - 2 : NSTAGE - 1;   // prefetch distance in tiles
+    static_assert(PD >= 1, "ring too shallow");
+    static_assert(PD * 2 * NDMA < 64, "too many loads in flight for vmcnt");
 
-    __shared__ __attribute__((aligned(1024))) char smem[4 * TILE_B];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // 2 * NSTAGE * TILE_B bytes
     char *const Ks = smem;
-    char *const Vs = smem + 2 * TILE_B;
+    char *const Vs = smem + NSTAGE * TILE_B;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
+    const bool late = PP && wave >= NW / 2;   // this wave runs half a tile behind
 
     const int L = xcd_remap(blockIdx.x, gridDim.x);
     const int qb = L % a.nqb;
@@ -95,26 +135,42 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 #pragma unroll
         for (int s = 0; s < DS; ++s) qf[qi][s] = *(const bf16x8 *)(qp + 16 * s);
     }
+    // Consume the Q registers here, so that the wait for these loads sits before the loop and
+    // not inside it, where it would also wait for the tile loads in flight.
+#pragma unroll
+    for (int qi = 0; qi < QB; ++qi)
+#pragma unroll
+        for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qf[qi][s]));
 
-    u32x4 kr[LPT], vr[LPT];
-    auto gload = [&](int t) {
+    // Direct load i of this wave covers tile rows (wave*NDMA + i)*RPI .. +RPI-1; this lane lands
+    // on row drow[i], chunk position lane % CPR, and so fetches chunk (lane % CPR) ^ swz(row).
+    int drow[NDMA];
+    int64_t koff[NDMA], voff[NDMA];
+#pragma unroll
+    for (int i = 0; i < NDMA; ++i) {
+        drow[i] = (wave * NDMA + i) * RPI + lane / CPR;
+        koff[i] = drow[i] * k_rb + (((lane % CPR) ^ Swz<D>::k(drow[i])) << 4);
+        voff[i] = drow[i] * v_rb + (((lane % CPR) ^ Swz<D>::v(drow[i])) << 4);
+    }
+    auto issue = [&](int t, int stage) {
         const int key0 = t * BN;
+        const unsigned kdst = __builtin_amdgcn_readfirstlane(lds_offset(Ks) + stage * TILE_B + wave * (NDMA * 1024));
+        const unsigned vdst = kdst + NSTAGE * TILE_B;
+        if (key0 + BN <= a.NK) {
+            const char *kt = Kg + key0 * k_rb, *vt = Vg + key0 * v_rb;
 #pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-            const int cid = tid + NT * i;
-            const int r = cid / CPR, cc = cid % CPR;
-            const int gr = min(key0 + r, a.NK - 1);      // rows past the end repeat the last row (masked later)
-            kr[i] = *(const u32x4 *)(Kg + gr * k_rb + cc * 16);
-            vr[i] = *(const u32x4 *)(Vg + gr * v_rb + cc * 16);
-        }
-    };
-    auto sstore = [&](int buf) {
+            for (int i = 0; i < NDMA; ++i) {
+                direct_load_1k(kt + koff[i], kdst + i * 1024);
+                direct_load_1k(vt + voff[i], vdst + i * 1024);
+            }
+        } else {
+            // ragged last tile: rows past the end repeat the last row (their scores are masked)
 #pragma unroll
-        for (int i = 0; i < LPT; ++i) {
-            const int cid = tid + NT * i;
-            const int r = cid / CPR, cc = cid % CPR;
-            *(u32x4 *)(Ks + buf * TILE_B + r * ROWB + ((cc ^ Swz<D>::k(r)) << 4)) = kr[i];
-            *(u32x4 *)(Vs + buf * TILE_B + r * ROWB + ((cc ^ Swz<D>::v(r)) << 4)) = vr[i];
+            for (int i = 0; i < NDMA; ++i) {
+                const int64_t back = max(key0 + drow[i] - (a.NK - 1), 0);
+                direct_load_1k(Kg + (key0 - back) * k_rb + koff[i], kdst + i * 1024);
+                direct_load_1k(Vg + (key0 - back) * v_rb + voff[i], vdst + i * 1024);
+            }
         }
     };
 
@@ -135,40 +191,42 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     const float thr = 8.0f / a.c;
 
     const int i16 = lane & 15, blk1 = (lane >> 4) & 1;
+    bf16x8 pb[QB][2][2];   // softmax weights of the current tile, B-operand order
 
-    if (t0 < t1) gload(t0);
-    for (int t = t0; t < t1; ++t) {
-        const int buf = (t - t0) & 1;
-        sstore(buf);
-        __syncthreads();
-        if (t + 1 < t1) gload(t + 1);
-        const int key0 = t * BN;
-        if (CAUSAL && key0 > qrow0 + QB * 32 - 1) continue;   // tile lies after every row of this wave
-
-        const char *Kt = Ks + buf * TILE_B;
-        const char *Vt = Vs + buf * TILE_B;
-
-        // ---- S^T = K Q^T
+    // ---- scores and online softmax of one tile: S^T = K Q^T, mask, update m/l, weights -> pb
+    auto scores_softmax = [&](const char *Kt, int key0) {
+        // The K fragments of KPF 32-key blocks are requested from LDS before the first product
+        // so that the reads overlap the matrix-core work instead of serialising with it.
         f32x16 sacc[QB][2];
+        constexpr int KPF = QB == 1 ? 2 : 1;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb0 = 0; kb0 < 2; kb0 += KPF) {
+            bf16x8 kf[KPF][DS];
 #pragma unroll
-            for (int qi = 0; qi < QB; ++qi)
+            for (int kk = 0; kk < KPF; ++kk) {
+                const int key = (kb0 + kk) * 32 + j;
+                const char *krow = Kt + key * ROWB;
+                const int ksw = Swz<D>::k(key);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sacc[qi][kb][v] = 0.f;
-            const int key = kb * 32 + j;
-            const char *krow = Kt + key * ROWB;
-            const int ksw = Swz<D>::k(key);
+                for (int s = 0; s < DS; ++s) kf[kk][s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
+            }
+            if (QB == 1) __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the products
 #pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                const bf16x8 kf = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
+            for (int kk = 0; kk < KPF; ++kk) {
+                const int kb = kb0 + kk;
 #pragma unroll
                 for (int qi = 0; qi < QB; ++qi)
-                    sacc[qi][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qi][s], sacc[qi][kb], 0, 0, 0);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sacc[qi][kb][v] = 0.f;
+#pragma unroll
+                for (int s = 0; s < DS; ++s)
+#pragma unroll
+                    for (int qi = 0; qi < QB; ++qi)
+                        sacc[qi][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][s], qf[qi][s], sacc[qi][kb], 0, 0, 0);
             }
         }
 
-        // ---- mask: keys past the end of the tensor, and (causal) keys after the query row
+        // mask: keys past the end of the tensor, and (causal) keys after the query row
         const bool ragged = key0 + BN > a.NK;
         const bool diag = CAUSAL && (key0 + BN - 1 > qrow0);
         if (ragged || diag) {
@@ -186,8 +244,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
             }
         }
 
-        // ---- online softmax, weights to bf16 in B-operand order
-        bf16x8 pb[QB][2][2];
 #pragma unroll
         for (int qi = 0; qi < QB; ++qi) {
             float mx = sacc[qi][0][0];
@@ -224,8 +280,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) pb[qi][kb][t2][e] = (__bf16)sacc[qi][kb][8 * t2 + e];
         }
+    };
 
-        // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T for the tile whose weights are in pb
+    auto accumulate = [&](const char *Vt) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -248,7 +306,39 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
                         oacc[qi][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[qi][kb][t2], oacc[qi][db], 0, 0, 0);
                 }
             }
+    };
+
+    // A tile is skipped by a wave when it lies after every row the wave owns (causal only).
+    auto active = [&](int t) { return !CAUSAL || t * BN <= qrow0 + QB * 32 - 1; };
+
+    // Ring protocol.  Before the loop the loads of tiles t0 .. t0+PD-1 are issued.  Iteration t
+    // waits until this wave's loads of tile t have landed, meets the other waves at the barrier
+    // (now the whole tile is visible, and every wave has finished reading tile t-1, or tile t-2
+    // for the value product of the late waves), then issues the loads of tile t+PD into the
+    // stage that was released, and computes on tile t.
+    constexpr int PER_TILE = 2 * NDMA;
+#pragma unroll
+    for (int s = 0; s < PD; ++s)
+        if (t0 + s < t1) issue(t0 + s, s);
+    bool pending = false;   // late waves: pb holds weights whose value product is still due
+    for (int t = t0; t < t1; ++t) {
+        const int n = t - t0;
+        if (t + PD - 1 < t1) wait_vmcnt<(PD - 1) * PER_TILE>();   // PD-1 younger tiles may still fly
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (t + PD < t1) issue(t + PD, (n + PD) % NSTAGE);
+        const char *Kt = Ks + (n % NSTAGE) * TILE_B;
+        const char *Vt = Vs + (n % NSTAGE) * TILE_B;
+        if (late) {
+            if (pending) accumulate(Vs + ((n + NSTAGE - 1) % NSTAGE) * TILE_B);
+            pending = active(t);
+            if (pending) scores_softmax(Kt, t * BN);
+        } else if (active(t)) {
+            scores_softmax(Kt, t * BN);
+            accumulate(Vt);
+        }
     }
+    if (late && pending) accumulate(Vs + ((t1 - t0 - 1) % NSTAGE) * TILE_B);
 
     // ---- epilogue.  Accumulator register v of block db is d = 32*db + 8*(v/4) + 4*h + v%4.
 #pragma unroll
@@ -276,7 +366,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
                         *(f32x4 *)((float *)a.O + off + d) = o;
                     }
                 }
-            if (a.lse && h == 0) a.lse[(int64_t)bh * a.W + row] = m[qi] * a.scale + __logf(lt);
+            if (a.lse && h == 0) a.lse[(int64_t)bh * a.W + row] = m[qi] * a.scale + logf(lt);
         } else {
             const int64_t slot = (int64_t)bh * a.nparts + a.part0 + (CAUSAL ? 0 : split);
             float *op = a.Opart + (slot * a.W + row) * D;

@@ -3,6 +3,7 @@
 #include "tlinattn.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 #include <mutex>
 #include <utility>
@@ -164,18 +165,31 @@ Workspace carve(void *ws, const tlin_params *p, int nparts)
     return {base, base + rows * p->D, base + rows * p->D + rows};
 }
 
-template <int D, int NW, int QB, bool CAUSAL>
-void launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
+template <int D, int NW, int QB, bool CAUSAL, bool PP, int NSTAGE>
+tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NW, QB, CAUSAL>), dim3(grid), dim3(NW * 64), 0, st, a);
+    constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
+    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
+    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, PP, NSTAGE>;
+    if (lds_bytes > 64 * 1024) {
+        // more than 64 KB of dynamic LDS has to be allowed once per kernel
+        static std::once_flag once;
+        static hipError_t err = hipSuccess;
+        std::call_once(once, [&] {
+            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        });
+        if (err != hipSuccess) return TLIN_ERR_HIP;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
+    return TLIN_OK;
 }
 
 template <int D, bool CAUSAL>
-void launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
+tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    if (s.nw == 8) launch_bf16_shape<D, 8, 1, CAUSAL>(a, grid, st);
-    else if (s.nw == 4) launch_bf16_shape<D, 4, 1, CAUSAL>(a, grid, st);
-    else launch_bf16_shape<D, 2, 1, CAUSAL>(a, grid, st);
+    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, false, 4>(a, grid, st);
+    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, false, 4>(a, grid, st);
+    return launch_bf16_shape<D, 2, 1, CAUSAL, false, 4>(a, grid, st);
 }
 
 // Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
@@ -189,8 +203,10 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
     LaunchTimer timer(causal ? KC_WINDOW : KC_HISTORY, st);
     if (p->in_dtype == TLIN_BF16) {
         const Shape s = bf16_shape(p->W);
-        if (p->D == 128) causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
-        else causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
+        tlin_status rc;
+        if (p->D == 128) rc = causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
+        else rc = causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
+        if (rc != TLIN_OK) return rc;
     } else {
         if (p->D == 128) {
             if (causal) hipLaunchKernelGGL((attn_f32_kernel<128, true>), dim3(grid), dim3(256), 0, st, a);
@@ -234,6 +250,7 @@ AttnArgs base_args(const tlin_params *p, const void *Q, const void *K, const voi
     a.nsplit = 1; a.tiles_per_split = 0x3fffffff;
     a.scale = p->scale;
     a.c = p->scale * 1.4426950408889634f;
+    a.pp_mode = getenv("TLIN_PP") ? atoi(getenv("TLIN_PP")) : 0;
     return a;
 }
 
