@@ -42,7 +42,6 @@ struct AttnArgs {
     float *lse;                 // nullable, dense [BH][W]
     int32_t out_bf16;
     int32_t direct;
-    int32_t pp_mode;
 };
 
 struct MergeArgs {

@@ -3,13 +3,13 @@
 #include "tlinattn.h"
 
 #include <math.h>
-#include <stdlib.h>
 
 #include <mutex>
 #include <utility>
 #include <vector>
 
 #include "attn_bf16.h"
+#include "attn_bf16_pp.h"
 #include "attn_f32.h"
 #include "merge.h"
 
@@ -184,10 +184,34 @@ tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
     return TLIN_OK;
 }
 
+template <int D, int NW, int NSTAGE>
+tlin_status launch_bf16_pp(const AttnArgs &a, int grid, hipStream_t st)
+{
+    constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
+    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
+    auto kernel = attn_bf16_pp_kernel<D, NW, NSTAGE>;
+    if (lds_bytes > 64 * 1024) {
+        static std::once_flag once;
+        static hipError_t err = hipSuccess;
+        std::call_once(once, [&] {
+            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        });
+        if (err != hipSuccess) return TLIN_ERR_HIP;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
+    return TLIN_OK;
+}
+
+// Windows of more than 128 rows over history keys (no mask) take the ping-pong kernel: eight
+// waves, two per SIMD, in opposite phases.  Smaller windows (bandwidth bound) and the causal
+// window kernel keep the simpler per-tile schedule, which can skip tiles above the diagonal.
 template <int D, bool CAUSAL>
 tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, false, 4>(a, grid, st);
+    if (s.nw == 8) {
+        if (!CAUSAL) return launch_bf16_pp<D, 8, 4>(a, grid, st);
+        return launch_bf16_shape<D, 8, 1, CAUSAL, false, 4>(a, grid, st);
+    }
     if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, false, 4>(a, grid, st);
     return launch_bf16_shape<D, 2, 1, CAUSAL, false, 4>(a, grid, st);
 }
@@ -250,7 +274,6 @@ AttnArgs base_args(const tlin_params *p, const void *Q, const void *K, const voi
     a.nsplit = 1; a.tiles_per_split = 0x3fffffff;
     a.scale = p->scale;
     a.c = p->scale * 1.4426950408889634f;
-    a.pp_mode = getenv("TLIN_PP") ? atoi(getenv("TLIN_PP")) : 0;
     return a;
 }
 

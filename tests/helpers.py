@@ -12,8 +12,8 @@ BF16_MAX_ABS = 2e-2
 BF16_MEAN_ABS = 5e-3
 # The absolute bounds say little when the outputs themselves are tiny (near-uniform softmax over
 # small values), so the bf16 path must also meet a scale-free bound: rms error <= 1% of the rms
-# of the reference.  Rounding the weights and the output to bf16 (relative 2^-9 each, random
-# sign) gives about 0.2-0.3%.
+# of the reference.  Rounding the weights and the output to bf16 (relative error up to 2^-8 each,
+# random sign) gives about 0.2-0.4%.
 BF16_REL_RMS = 1e-2
 
 
