@@ -3,6 +3,7 @@
 #include "tlinattn.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 #include <mutex>
 #include <utility>
@@ -10,6 +11,7 @@
 
 #include "attn_bf16.h"
 #include "attn_bf16_pp.h"
+#include "attn_bf16_w64.h"
 #include "attn_f32.h"
 #include "merge.h"
 
@@ -26,7 +28,7 @@ struct Shape { int nw, qb; int bm() const { return nw * qb * 32; } };
 
 Shape bf16_shape(int W)
 {
-    if (W > 128) return {8, 1};
+    if (W > 128) return {4, 2};
     if (W > 64) return {4, 1};
     return {2, 1};
 }
@@ -39,7 +41,7 @@ int resident_wgs(int in_dtype, int W)
 {
     if (in_dtype == TLIN_F32) return kNumCU * 2;
     const Shape s = bf16_shape(W);
-    return kNumCU * (s.nw >= 8 ? 1 : 2);
+    return kNumCU * (s.bm() >= 256 ? 1 : 2);
 }
 
 // ---- measurement aid: per-kernel timing with HIP events on the launch stream
@@ -205,11 +207,34 @@ tlin_status launch_bf16_pp(const AttnArgs &a, int grid, hipStream_t st)
 // Windows of more than 128 rows over history keys (no mask) take the ping-pong kernel: eight
 // waves, two per SIMD, in opposite phases.  Smaller windows (bandwidth bound) and the causal
 // window kernel keep the simpler per-tile schedule, which can skip tiles above the diagonal.
+template <int D, int NW, int RB, int NSTAGE>
+tlin_status launch_bf16_w64(const AttnArgs &a, int grid, hipStream_t st)
+{
+    constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2 + NW * 4096;   // tile ring + 4 KB per wave for rescaling
+    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
+    auto kernel = attn_bf16_w64_kernel<D, NW, RB, NSTAGE>;
+    if (lds_bytes > 64 * 1024) {
+        static std::once_flag once;
+        static hipError_t err = hipSuccess;
+        std::call_once(once, [&] {
+            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        });
+        if (err != hipSuccess) return TLIN_ERR_HIP;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
+    return TLIN_OK;
+}
+
 template <int D, bool CAUSAL>
 tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    if (s.nw == 8) {
-        if (!CAUSAL) return launch_bf16_pp<D, 8, 4>(a, grid, st);
+    if (s.bm() == 256) {
+        if (!CAUSAL && getenv("TLIN_KERNEL")) {   // experimental kernels, selected by hand
+            const int k = atoi(getenv("TLIN_KERNEL"));
+            if (k == 1) return launch_bf16_w64<D, 4, 2, 4>(a, grid, st);
+            if (k == 2) return launch_bf16_w64<D, 8, 1, 4>(a, grid, st);
+            if (k == 3) return launch_bf16_pp<D, 8, 4>(a, grid, st);
+        }
         return launch_bf16_shape<D, 8, 1, CAUSAL, false, 4>(a, grid, st);
     }
     if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, false, 4>(a, grid, st);
