@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="latency-vs-N sweep instead of the single workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy, so that a rocprofv3 --pmc run of this "
+                         "command shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -114,6 +117,13 @@ def main():
         return tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=combine, scale=w.scale, num_splits=args.num_splits,
                                   workspace=ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     sec = time_steps(step, args.steps, args.warmup, torch)
 
     # Per-kernel durations: the same K steps again with event pairs around every launch.
@@ -166,15 +176,16 @@ def main():
     print(json.dumps(out), flush=True)
 
 
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (two runs of this script with --calibrate-copy; raw readings, commands and the scale factors of the
+# two counters are in profiles/attn_bf16_history_cfg4_pmc.md).  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg4_bf16_N131072_W512": 2_101_398 * 1024 + 33_280 * 1024,   # 2.004 GiB fetched + 32.5 MiB written
+}
+
+
 def measured_traffic(name):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
-    (profiles/hbm_traffic.json), or None when no measurement exists for this workload."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(name, {}).get("bytes_per_launch")
-    except (OSError, ValueError):
-        return None
+    return MEASURED_TRAFFIC_BYTES.get(name)
 
 
 def sweep(args, ti, tl, binding, torch, np, combine):

@@ -21,15 +21,10 @@
 //     transpose).  Two such reads form one 8-element operand.
 //   * K/V tiles of 64 keys go HBM -> LDS directly (global_load_lds_dwordx4: each wave
 //     instruction moves 1 KB, lane i landing at base + 16*i) through a ring of NSTAGE tiles,
-//     with the loads of the next NSTAGE-1 tiles in flight during compute: one workgroup per CU
-//     has to keep ~100 KB outstanding to cover HBM latency at full bandwidth.  One barrier per
-//     tile; completion is tracked by hand with s_waitcnt vmcnt.
-//   * Ping-pong (PP): with two waves per SIMD, the upper half of the waves runs half a tile out
-//     of phase - in the interval after barrier t it first finishes tile t-1 (value product)
-//     and then does scores and softmax of tile t, while the lower half does scores, softmax
-//     and value product of tile t.  The SIMD then has one wave in a matrix-core phase while
-//     the other is in its softmax (vector ALU) phase, instead of both alternating in lockstep.
-//     V tiles live one interval longer, so the prefetch distance is one tile shorter.
+//     the loads of the following tiles being in flight during compute.  One barrier per tile;
+//     completion is tracked by hand with s_waitcnt vmcnt.  (A compute unit keeps only some
+//     16-32 KB of such loads in flight; a wave that issues into a full queue waits there, so
+//     the ring depth beyond two tiles buys little.)
 //   * LDS rows are XOR-swizzled at 16-byte-chunk granularity so that the ds_read_b128 of the
 //     K operand and the transposed reads of V are bank-conflict free on the 64-bank LDS.  The
 //     direct loads write LDS linearly, so the swizzle is applied on the source side: the lane
@@ -51,6 +46,7 @@ template <> struct Swz<64> {    // 128-byte rows, 8 chunks; two rows per 256-byt
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 // One wave-wide direct load: 64 lanes x 16 bytes from per-lane global addresses to the 1 KB of
 // LDS starting at the wave-uniform byte offset lds_base (lane i lands at lds_base + 16*i).
@@ -76,7 +72,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int NW, int QB, bool CAUSAL, bool PP, int NSTAGE>
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 {
     constexpr int BN = 64;                 // keys per tile
@@ -87,10 +83,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     constexpr int RPI = 1024 / ROWB;       // rows moved by one wave-wide direct load
     constexpr int NDMA = BN / RPI / NW;    // direct loads per wave per tensor per tile
     static_assert(BN % (RPI * NW) == 0 && NDMA >= 1, "tile does not divide over the waves");
-    static_assert(!PP || NW % 2 == 0, "ping-pong needs an even number of waves");
     constexpr int DS = D / 16;             // contraction steps of Q K^T
     constexpr int DB = D / 32;             // 32-row blocks of O^T
-    constexpr int PD = PP ? NSTAGE - 2 : NSTAGE - 1;   // prefetch distance in tiles
+    constexpr int PD = NSTAGE - 1;         // prefetch distance in tiles
     static_assert(PD >= 1, "ring too shallow");
     static_assert(PD * 2 * NDMA < 64, "too many loads in flight for vmcnt");
 
@@ -101,7 +96,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
-    const bool late = PP && wave >= NW / 2;   // this wave runs half a tile behind
 
     const int L = xcd_remap(blockIdx.x, gridDim.x);
     const int qb = L % a.nqb;
@@ -189,6 +183,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     // 2^8 in the exponent: weights then stay <= 256, and the accumulator is rescaled rarely.
     // Any reference point gives the same normalised result, so this is exact.
     const float thr = 8.0f / a.c;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
     const int i16 = lane & 15, blk1 = (lane >> 4) & 1;
     bf16x8 pb[QB][2][2];   // softmax weights of the current tile, B-operand order
@@ -198,7 +193,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
         // The K fragments of KPF 32-key blocks are requested from LDS before the first product
         // so that the reads overlap the matrix-core work instead of serialising with it.
         f32x16 sacc[QB][2];
-        constexpr int KPF = QB == 1 ? 2 : 1;
+        constexpr int KPF = (QB == 1 && !(CAUSAL && D == 128)) ? 2 : 1;
 #pragma unroll
         for (int kb0 = 0; kb0 < 2; kb0 += KPF) {
             bf16x8 kf[KPF][DS];
@@ -210,7 +205,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 #pragma unroll
                 for (int s = 0; s < DS; ++s) kf[kk][s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
             }
-            if (QB == 1) __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the products
+            if (KPF == 2) __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the products
 #pragma unroll
             for (int kk = 0; kk < KPF; ++kk) {
                 const int kb = kb0 + kk;
@@ -263,22 +258,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
                 m[qi] = mn;
             }
             const float mc = (m[qi] == -INFINITY) ? 0.f : m[qi] * a.c;
+            // weights, rounded to bf16; the row sum is accumulated from the rounded values (the ones
+            // the value product uses) with v_dot2c_f32_bf16 against (1, 1): two weights per instruction
             float ls = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float p = fast_exp2(fmaf(sacc[qi][kb][v], a.c, -mc));
-                    ls += p;
-                    sacc[qi][kb][v] = p;
-                }
-            l[qi] += ls;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pb[qi][kb][t2][e] = (__bf16)sacc[qi][kb][8 * t2 + e];
+                    for (int e = 0; e < 8; e += 2) {
+                        const __bf16 p0 = (__bf16)fast_exp2(fmaf(sacc[qi][kb][8 * t2 + e], a.c, -mc));
+                        const __bf16 p1 = (__bf16)fast_exp2(fmaf(sacc[qi][kb][8 * t2 + e + 1], a.c, -mc));
+                        pb[qi][kb][t2][e] = p0;
+                        pb[qi][kb][t2][e + 1] = p1;
+                        const bf16x2 pp = {p0, p1};
+                        ls = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ls, false);
+                    }
+            l[qi] += ls;
         }
     };
 
@@ -313,32 +309,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 
     // Ring protocol.  Before the loop the loads of tiles t0 .. t0+PD-1 are issued.  Iteration t
     // waits until this wave's loads of tile t have landed, meets the other waves at the barrier
-    // (now the whole tile is visible, and every wave has finished reading tile t-1, or tile t-2
-    // for the value product of the late waves), then issues the loads of tile t+PD into the
+    // (now the whole tile is visible, and every wave has finished reading tile t-1), then issues the loads of tile t+PD into the
     // stage that was released, and computes on tile t.
     constexpr int PER_TILE = 2 * NDMA;
 #pragma unroll
     for (int s = 0; s < PD; ++s)
         if (t0 + s < t1) issue(t0 + s, s);
-    bool pending = false;   // late waves: pb holds weights whose value product is still due
     for (int t = t0; t < t1; ++t) {
         const int n = t - t0;
         if (t + PD - 1 < t1) wait_vmcnt<(PD - 1) * PER_TILE>();   // PD-1 younger tiles may still fly
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         if (t + PD < t1) issue(t + PD, (n + PD) % NSTAGE);
-        const char *Kt = Ks + (n % NSTAGE) * TILE_B;
-        const char *Vt = Vs + (n % NSTAGE) * TILE_B;
-        if (late) {
-            if (pending) accumulate(Vs + ((n + NSTAGE - 1) % NSTAGE) * TILE_B);
-            pending = active(t);
-            if (pending) scores_softmax(Kt, t * BN);
-        } else if (active(t)) {
-            scores_softmax(Kt, t * BN);
-            accumulate(Vt);
+        if (active(t)) {
+            scores_softmax(Ks + (n % NSTAGE) * TILE_B, t * BN);
+            accumulate(Vs + (n % NSTAGE) * TILE_B);
         }
     }
-    if (late && pending) accumulate(Vs + ((t1 - t0 - 1) % NSTAGE) * TILE_B);
 
     // ---- epilogue.  Accumulator register v of block db is d = 32*db + 8*(v/4) + 4*h + v%4.
 #pragma unroll

@@ -3,15 +3,12 @@
 #include "tlinattn.h"
 
 #include <math.h>
-#include <stdlib.h>
 
 #include <mutex>
 #include <utility>
 #include <vector>
 
 #include "attn_bf16.h"
-#include "attn_bf16_pp.h"
-#include "attn_bf16_w64.h"
 #include "attn_f32.h"
 #include "merge.h"
 
@@ -28,7 +25,7 @@ struct Shape { int nw, qb; int bm() const { return nw * qb * 32; } };
 
 Shape bf16_shape(int W)
 {
-    if (W > 128) return {4, 2};
+    if (W > 128) return {8, 1};
     if (W > 64) return {4, 1};
     return {2, 1};
 }
@@ -167,53 +164,14 @@ Workspace carve(void *ws, const tlin_params *p, int nparts)
     return {base, base + rows * p->D, base + rows * p->D + rows};
 }
 
-template <int D, int NW, int QB, bool CAUSAL, bool PP, int NSTAGE>
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE>
 tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, PP, NSTAGE>;
+    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE>;
     if (lds_bytes > 64 * 1024) {
         // more than 64 KB of dynamic LDS has to be allowed once per kernel
-        static std::once_flag once;
-        static hipError_t err = hipSuccess;
-        std::call_once(once, [&] {
-            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        });
-        if (err != hipSuccess) return TLIN_ERR_HIP;
-    }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
-    return TLIN_OK;
-}
-
-template <int D, int NW, int NSTAGE>
-tlin_status launch_bf16_pp(const AttnArgs &a, int grid, hipStream_t st)
-{
-    constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
-    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_pp_kernel<D, NW, NSTAGE>;
-    if (lds_bytes > 64 * 1024) {
-        static std::once_flag once;
-        static hipError_t err = hipSuccess;
-        std::call_once(once, [&] {
-            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        });
-        if (err != hipSuccess) return TLIN_ERR_HIP;
-    }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
-    return TLIN_OK;
-}
-
-// Windows of more than 128 rows over history keys (no mask) take the ping-pong kernel: eight
-// waves, two per SIMD, in opposite phases.  Smaller windows (bandwidth bound) and the causal
-// window kernel keep the simpler per-tile schedule, which can skip tiles above the diagonal.
-template <int D, int NW, int RB, int NSTAGE>
-tlin_status launch_bf16_w64(const AttnArgs &a, int grid, hipStream_t st)
-{
-    constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2 + NW * 4096;   // tile ring + 4 KB per wave for rescaling
-    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_w64_kernel<D, NW, RB, NSTAGE>;
-    if (lds_bytes > 64 * 1024) {
         static std::once_flag once;
         static hipError_t err = hipSuccess;
         std::call_once(once, [&] {
@@ -228,17 +186,9 @@ tlin_status launch_bf16_w64(const AttnArgs &a, int grid, hipStream_t st)
 template <int D, bool CAUSAL>
 tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    if (s.bm() == 256) {
-        if (!CAUSAL && getenv("TLIN_KERNEL")) {   // experimental kernels, selected by hand
-            const int k = atoi(getenv("TLIN_KERNEL"));
-            if (k == 1) return launch_bf16_w64<D, 4, 2, 4>(a, grid, st);
-            if (k == 2) return launch_bf16_w64<D, 8, 1, 4>(a, grid, st);
-            if (k == 3) return launch_bf16_pp<D, 8, 4>(a, grid, st);
-        }
-        return launch_bf16_shape<D, 8, 1, CAUSAL, false, 4>(a, grid, st);
-    }
-    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, false, 4>(a, grid, st);
-    return launch_bf16_shape<D, 2, 1, CAUSAL, false, 4>(a, grid, st);
+    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, 4>(a, grid, st);
+    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, 4>(a, grid, st);
+    return launch_bf16_shape<D, 2, 1, CAUSAL, 4>(a, grid, st);
 }
 
 // Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
