@@ -38,6 +38,13 @@ def parse():
     ap.add_argument("--combine", choices=("sum", "joint"), default="sum")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--sweep", action="store_true", help="latency-vs-N sweep instead of the single workload")
+    ap.add_argument("--workload", choices=("config", "decode", "restore"), default="config",
+                    help="config: --config's layer call (default). decode: the cache-hit step of Section 4.2, "
+                         "--W newest rows (default 1) query --N history rows (default 131072) through "
+                         "tlin_history_attn. restore: the context path's last layer, --N history rows (default "
+                         "131072) query --W compressed rows (default 256) through tlin_history_attn")
+    ap.add_argument("--N", type=int, default=None)
+    ap.add_argument("--W", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -65,20 +72,26 @@ def time_steps(fn, steps, warmup, torch):
     return (time.perf_counter() - t0) / steps
 
 
-def cpu_baseline(w, host, target_s, oracle, np):
-    """Oracle layer (SUM: one history softmax plus one window softmax per row) on a seeded row
-    sample sized for about target_s seconds; returns the JSON object."""
+def cpu_baseline(w, host, target_s, oracle, np, layer=True):
+    """Oracle on a seeded row sample sized for about target_s seconds; returns the JSON object.
+    layer=True: the layer call (SUM: one history softmax plus one window softmax per row);
+    layer=False: history attention only."""
+    def run(rows):
+        if layer:
+            oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM, rows)
+        else:
+            oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)
     rng = np.random.default_rng(12345)
     probe = np.sort(rng.choice(w.W, size=min(w.W, 1), replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM, probe)
+    run(probe)
     t_probe = time.perf_counter() - t0            # B*H rows in parallel over the cores
     rows_per_head = int(max(1, min(w.W, target_s / max(t_probe, 1e-4) * len(probe))))
     rows = np.sort(rng.choice(w.W, size=rows_per_head, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM, rows)
+    run(rows)
     dt = time.perf_counter() - t0
-    flops = 4.0 * w.B * w.H * w.D * (len(rows) * w.N + float(np.sum(rows + 1)))
+    flops = 4.0 * w.B * w.H * w.D * (len(rows) * w.N + (float(np.sum(rows + 1)) if layer else 0.0))
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"{len(rows)} of {w.W} window rows in each of {w.B * w.H} heads, full history, fp64, "
                       f"{dt:.1f} s",
@@ -107,15 +120,33 @@ def main():
     if args.sweep:
         return sweep(args, ti, tl, binding, torch, np, combine)
 
-    w = ti.config(args.config - 1)
-    host = ti.make(w)
+    layer = args.workload == "config"
+    if layer:
+        w = ti.config(args.config - 1)
+        metric = "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak"
+        what = "tlin_layer_attn = history partitions + window causal + merge"
+    elif args.workload == "decode":
+        w = ti.decode_point(args.N or 131072, args.W or 1)
+        metric = "cache-hit step: newest rows x N-row history, bf16; % HBM peak"
+        what = "tlin_history_attn = history partitions + merge"
+    else:
+        w = ti.restore_point(args.N or 131072, args.W or 256)
+        metric = "context-path restoration: N query rows x W_oh compressed rows, bf16"
+        what = "tlin_history_attn, one partition"
+    host = ti.make(w) if layer else ti.make(w, which=("Q", "Kh", "Vh"))
     dev = upload(host, w.dtype, ti, torch, np)
-    Q, Kh, Vh, Kw, Vw = (dev[k] for k in ("Q", "Kh", "Vh", "Kw", "Vw"))
+    Q, Kh, Vh = dev["Q"], dev["Kh"], dev["Vh"]
     ws = tl.Workspace()
 
-    def step():
-        return tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=combine, scale=w.scale, num_splits=args.num_splits,
-                                  workspace=ws)
+    if layer:
+        Kw, Vw = dev["Kw"], dev["Vw"]
+
+        def step():
+            return tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=combine, scale=w.scale,
+                                      num_splits=args.num_splits, workspace=ws)
+    else:
+        def step():
+            return tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale, num_splits=args.num_splits, workspace=ws)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -137,10 +168,14 @@ def main():
     win_ms = ms[1] / max(launches[1], 1)
     merge_ms = ms[2] / max(launches[2], 1)
 
-    flops_h, flops_w = w.flops_history(), w.flops_window()
+    flops_h, flops_w = w.flops_history(), (w.flops_window() if layer else 0.0)
     tflops = (flops_h + flops_w) / sec / 1e12
     esz = 4 if w.dtype == ti.F32 else 2
-    kv_bytes = 2.0 * w.B * w.H * w.N * w.D * esz              # K_hist + V_hist, each read once
+    # Algorithmic bytes of the history kernel: K_hist + V_hist read once; where the query side is
+    # the long one (restoration) Q read once and O written once dominate and are counted too.
+    kv_bytes = 2.0 * w.B * w.H * w.N * w.D * esz
+    if args.workload == "restore":
+        kv_bytes += 2.0 * w.B * w.H * w.W * w.D * esz
     hist_tflops = flops_h / (hist_ms * 1e-3) / 1e12
     hist_gbs = kv_bytes / (hist_ms * 1e-3) / 1e9
     # Arithmetic intensity of the history kernel is W flop/byte (bf16): it is matrix-core bound
@@ -148,7 +183,7 @@ def main():
     # vector ALUs.
     if w.dtype == ti.F32:
         roof = {"bound": "alu", "achieved": hist_tflops, "peak": PEAK_F32_VALU_TFLOPS, "unit": "TFLOP/s"}
-    elif w.W >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+    elif flops_h / kv_bytes >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         roof = {"bound": "mfma", "achieved": hist_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": hist_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
@@ -158,21 +193,22 @@ def main():
     roof["traffic"] = measured_traffic(w.name)
 
     out = {
-        "metric": "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak",
+        "metric": metric,
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == ti.F32 else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "D": w.D, "N_history": w.N, "W_window": w.W,
                    "combine": args.combine, "num_splits": binding.num_splits(tl.params_for(Q, w.N, num_splits=args.num_splits)),
-                   "step": "tlin_layer_attn = history partitions + window causal + merge"},
+                   "step": what},
         "window_tokens_per_s": w.B * w.W / sec, "context_tokens_per_s": w.B * w.N / sec,
         "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_MFMA_TFLOPS,
+        "step_GB_per_s": kv_bytes / sec / 1e9, "pct_hbm_peak": 100.0 * kv_bytes / sec / 1e9 / PEAK_HBM_GBS,
         "kernels_ms": {"history": hist_ms, "window_causal": win_ms, "merge": merge_ms},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
         import oracle
-        out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np)
+        out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np, layer)
     print(json.dumps(out), flush=True)
 
 

@@ -72,9 +72,14 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE>
+// RESIDENT: the whole key/value partition (at most NSTAGE tiles) is loaded into LDS once and the
+// workgroup then walks over query blocks qb, qb + q_groups, ... without any further barrier, so
+// its waves drift apart and one wave's matrix work overlaps another's softmax arithmetic.  Used
+// where the query side is the long one.
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 {
+    static_assert(!(RESIDENT && CAUSAL), "the resident variant is for unmasked attention");
     constexpr int BN = 64;                 // keys per tile
     constexpr int BM = NW * QB * 32;       // query rows per workgroup
     constexpr int ROWB = D * 2;            // bytes per K/V row
@@ -98,8 +103,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     const int j = lane & 31, h = lane >> 5;
 
     const int L = xcd_remap(blockIdx.x, gridDim.x);
-    const int qb = L % a.nqb;
-    const int rest = L / a.nqb;
+    const int qstep = RESIDENT ? a.q_groups : a.nqb;   // workgroups along the query axis of one head
+    int qb = L % qstep;
+    const int rest = L / qstep;
     const int split = rest % a.nsplit;
     const int bh = rest / a.nsplit;
     const int b = bh / a.H, hd = bh % a.H;
@@ -119,22 +125,25 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     const char *Vg = (const char *)((const __bf16 *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh);
     const int64_t k_rb = a.k_sr * 2, v_rb = a.v_sr * 2;
 
-    // Q^T fragments (B operand): lane holds query j, contraction elements 16*s + 8*h .. +7.
-    const int qrow0 = qb * BM + wave * (QB * 32);
+    int qrow0 = qb * BM + wave * (QB * 32);
     bf16x8 qf[QB][DS];
+    // Q^T fragments (B operand): lane holds query j, contraction elements 16*s + 8*h .. +7.
+    auto load_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int qi = 0; qi < QB; ++qi) {
-        const int r = min(qrow0 + qi * 32 + j, a.W - 1);
-        const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
+        for (int qi = 0; qi < QB; ++qi) {
+            const int r = min(qrow0 + qi * 32 + j, a.W - 1);
+            const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
 #pragma unroll
-        for (int s = 0; s < DS; ++s) qf[qi][s] = *(const bf16x8 *)(qp + 16 * s);
-    }
-    // Consume the Q registers here, so that the wait for these loads sits before the loop and
-    // not inside it, where it would also wait for the tile loads in flight.
+            for (int s = 0; s < DS; ++s) qf[qi][s] = *(const bf16x8 *)(qp + 16 * s);
+        }
+        // Consume the Q registers here, so that the wait for these loads sits before the tile loop
+        // and not inside it, where it would also wait for the tile loads in flight.
 #pragma unroll
-    for (int qi = 0; qi < QB; ++qi)
+        for (int qi = 0; qi < QB; ++qi)
 #pragma unroll
-        for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qf[qi][s]));
+            for (int s = 0; s < DS; ++s) asm volatile("" : "+v"(qf[qi][s]));
+    };
+    if (!RESIDENT) load_q();
 
     // Direct load i of this wave covers tile rows (wave*NDMA + i)*RPI .. +RPI-1; this lane lands
     // on row drow[i], chunk position lane % CPR, and so fetches chunk (lane % CPR) ^ swz(row).
@@ -170,15 +179,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 
     f32x16 oacc[QB][DB];
     float m[QB], l[QB];
+    auto reset = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int qi = 0; qi < QB; ++qi) {
-        m[qi] = -INFINITY;
-        l[qi] = 0.f;
+        for (int qi = 0; qi < QB; ++qi) {
+            m[qi] = -INFINITY;
+            l[qi] = 0.f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[qi][db][v] = 0.f;
-    }
+                for (int v = 0; v < 16; ++v) oacc[qi][db][v] = 0.f;
+        }
+    };
+    reset();
     // The running maximum is only advanced when a row's tile maximum exceeds it by more than
     // 2^8 in the exponent: weights then stay <= 256, and the accumulator is rescaled rarely.
     // Any reference point gives the same normalised result, so this is exact.
@@ -312,18 +324,47 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     // (now the whole tile is visible, and every wave has finished reading tile t-1), then issues the loads of tile t+PD into the
     // stage that was released, and computes on tile t.
     constexpr int PER_TILE = 2 * NDMA;
+    if (RESIDENT) {
+        // the partition has at most NSTAGE tiles (checked by the host): tile t lives in stage t
 #pragma unroll
-    for (int s = 0; s < PD; ++s)
-        if (t0 + s < t1) issue(t0 + s, s);
-    for (int t = t0; t < t1; ++t) {
-        const int n = t - t0;
-        if (t + PD - 1 < t1) wait_vmcnt<(PD - 1) * PER_TILE>();   // PD-1 younger tiles may still fly
-        else wait_vmcnt<0>();
+        for (int s = 0; s < NSTAGE; ++s)
+            if (s < t1) issue(s, s);
+        load_q();
+        wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (t + PD < t1) issue(t + PD, (n + PD) % NSTAGE);
-        if (active(t)) {
-            scores_softmax(Ks + (n % NSTAGE) * TILE_B, t * BN);
-            accumulate(Vs + (n % NSTAGE) * TILE_B);
+    } else {
+#pragma unroll
+        for (int s = 0; s < PD; ++s)
+            if (t0 + s < t1) issue(t0 + s, s);
+    }
+  do {
+    bf16x8 qn[QB][DS];   // resident variant: the next block's queries, requested before this block's work
+    if (RESIDENT) {
+        if (qb + qstep < a.nqb) {
+            const int nrow0 = (qb + qstep) * BM + wave * (QB * 32);
+#pragma unroll
+            for (int qi = 0; qi < QB; ++qi) {
+                const int r = min(nrow0 + qi * 32 + j, a.W - 1);
+                const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
+#pragma unroll
+                for (int s = 0; s < DS; ++s) qn[qi][s] = *(const bf16x8 *)(qp + 16 * s);
+            }
+        }
+        for (int t = 0; t < t1; ++t) {
+            scores_softmax(Ks + t * TILE_B, t * BN);
+            accumulate(Vs + t * TILE_B);
+        }
+    } else {
+        for (int t = t0; t < t1; ++t) {
+            const int n = t - t0;
+            if (t + PD - 1 < t1) wait_vmcnt<(PD - 1) * PER_TILE>();   // PD-1 younger tiles may still fly
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            if (t + PD < t1) issue(t + PD, (n + PD) % NSTAGE);
+            if (active(t)) {
+                scores_softmax(Ks + (n % NSTAGE) * TILE_B, t * BN);
+                accumulate(Vs + (n % NSTAGE) * TILE_B);
+            }
         }
     }
 
@@ -372,6 +413,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
             }
         }
     }
+    if (RESIDENT) {
+        qb += qstep;
+        if (qb < a.nqb) {
+            qrow0 = qb * BM + wave * (QB * 32);
+#pragma unroll
+            for (int qi = 0; qi < QB; ++qi)
+#pragma unroll
+                for (int s = 0; s < DS; ++s) qf[qi][s] = qn[qi][s];
+            reset();
+        }
+    }
+  } while (RESIDENT && qb < a.nqb);
 }
 
 }  // namespace tlin

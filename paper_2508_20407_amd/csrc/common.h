@@ -28,6 +28,7 @@ struct AttnArgs {
     int32_t W;                  // query rows
     int32_t NK;                 // key rows
     int32_t nqb;                // query blocks per head
+    int32_t q_groups;           // resident variant: workgroups per head; each takes blocks g, g+q_groups, ...
     int32_t nsplit;             // key partitions (1 for the causal kernel)
     int32_t tiles_per_split;    // key tiles (of 64 rows) per partition
     int32_t nparts;             // partial slots per (b,h) in the workspace

@@ -164,12 +164,12 @@ Workspace carve(void *ws, const tlin_params *p, int nparts)
     return {base, base + rows * p->D, base + rows * p->D + rows};
 }
 
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE>
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
 tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE>;
+    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>;
     if (lds_bytes > 64 * 1024) {
         // more than 64 KB of dynamic LDS has to be allowed once per kernel
         static std::once_flag once;
@@ -191,11 +191,39 @@ tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
     return launch_bf16_shape<D, 2, 1, CAUSAL, 4>(a, grid, st);
 }
 
+// Key tiles the resident variant keeps in LDS (128 KB of keys and values).
+int resident_tiles(int D) { return D == 128 ? 4 : 8; }
+
+// The resident variant pays when the key/value side fits in LDS as a whole and every workgroup
+// has several query blocks to walk over: long query side, short unsplit key side.
+bool use_resident(const tlin_params *p, bool causal, const AttnArgs &a)
+{
+    if (causal || p->in_dtype != TLIN_BF16 || !a.direct || a.nsplit != 1) return false;
+    if (bf16_shape(p->W).nw != 8) return false;
+    const int ntiles = (a.NK + 63) / 64;
+    const int64_t blocks = (int64_t)p->B * p->H * a.nqb;
+    return ntiles <= resident_tiles(p->D) && blocks >= 4 * (int64_t)kNumCU;
+}
+
 // Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
 tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream_t st)
 {
     const int qblk = query_block(p->in_dtype, p->W);
     a.nqb = (p->W + qblk - 1) / qblk;
+    if (use_resident(p, causal, a)) {
+        // one workgroup per compute unit, spread evenly over the heads
+        const int64_t bh = (int64_t)p->B * p->H;
+        int64_t g = (kNumCU + bh - 1) / bh;
+        if (g > a.nqb) g = a.nqb;
+        a.q_groups = (int)g;
+        const int64_t grid64 = bh * g;
+        if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
+        LaunchTimer timer(KC_HISTORY, st);
+        const tlin_status rc = p->D == 128 ? launch_bf16_shape<128, 8, 1, false, 4, true>(a, (int)grid64, st)
+                                           : launch_bf16_shape<64, 8, 1, false, 8, true>(a, (int)grid64, st);
+        if (rc != TLIN_OK) return rc;
+        return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+    }
     const int64_t grid64 = (int64_t)p->B * p->H * a.nqb * a.nsplit;
     if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     const int grid = (int)grid64;

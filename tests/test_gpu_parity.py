@@ -103,6 +103,63 @@ def test_degenerate_empty_history_is_standard_causal_attention():
         assert torch.equal(o, o_win)
 
 
+# ---------------------------------------------------------------- cache-hit and restoration shapes
+@pytest.mark.parametrize("W", [1, 2, 4, 8])
+def test_decode_shape_full_size_every_row(W):
+    """Cache-hit step (Section 4.2): the newest rows against the whole history, in the launch
+    configuration the bench times; also through the layer call with the W newest rows as window."""
+    run_all(ti.decode_point(131072, W))
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("W,N", [(1, 63), (1, 4097), (2, 1000), (3, 129), (5, 8191), (8, 2048)])
+def test_decode_shapes_ragged(dtype, D, W, N):
+    w = ti.Workload(f"decode_{dtype}_{D}_{W}_{N}", 2, 3, D, N, W, dtype, 1.0, 991 + W * 17 + N)
+    run_all(w)
+
+
+def test_restoration_shape_full_size_sampled_rows():
+    """Last layer of the context path (Section 3): every history row queries the W_oh = 256
+    compressed rows.  Many query blocks, one partition of four key tiles."""
+    w = ti.restore_point(131072, 256)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = upload(host, w.dtype)
+    rows = sample_rows(w.W, 40, seed=11)
+    o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, return_lse=True)
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)
+    idx = torch.from_numpy(rows).long().cuda()
+    assert_close(o[:, :, idx], ro, w.dtype, w.name)
+    np.testing.assert_allclose(to_host64(lse[:, :, idx]), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("n_queries,w_oh", [(5000, 256), (3001, 200), (1025, 64)])
+def test_restoration_shape_reduced_every_row(dtype, n_queries, w_oh):
+    w = ti.shrink(ti.restore_point(n_queries, w_oh), H=2, dtype=dtype)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = upload(host, w.dtype)
+    o = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale)
+    ro, _ = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, None)
+    assert_close(o, ro, w.dtype, w.name)
+
+
+@pytest.mark.parametrize("D,n_queries,w_oh", [(128, 33017, 256), (128, 32768, 200), (128, 40000, 1), (64, 33017, 512),
+                                               (64, 36000, 333)])
+def test_restoration_shape_keys_resident_in_lds_every_row(D, n_queries, w_oh):
+    """Enough query blocks per compute unit that the library keeps the whole key/value side in
+    LDS and lets every workgroup walk over several query blocks; ragged query and key tails."""
+    w = ti.shrink(ti.restore_point(n_queries, w_oh), H=8, D=D)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = upload(host, w.dtype)
+    o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, return_lse=True)
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, None)
+    assert_close(o, ro, w.dtype, w.name)
+    np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+    o32 = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, out_dtype=torch.float32)
+    assert_close(o32, ro, w.dtype, w.name + " f32 out")
+
+
 # ---------------------------------------------------------------- shapes, tails, degenerate cases
 @pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
 @pytest.mark.parametrize("D", [64, 128])

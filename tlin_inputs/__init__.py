@@ -106,6 +106,20 @@ def sweep_points():
     return pts
 
 
+def decode_point(N: int, W: int = 1) -> Workload:
+    """Cache-hit step (Section 4.2): only the newest W rows (1 in the paper) query an N-row history."""
+    return Workload(f"decode_bf16_N{N}_W{W}", 1, 32, 128, N, W, BF16, 1.0,
+                    _BASE_SEED + 6 + 7919 * N + 104729 * W)
+
+
+def restore_point(n_queries: int, w_oh: int = 256) -> Workload:
+    """Last layer of the context path (Section 3, restoration of the sequence length): every
+    history row queries the w_oh compressed rows.  In Workload terms W = n_queries query rows
+    and N = w_oh key/value rows."""
+    return Workload(f"restore_bf16_Q{n_queries}_K{w_oh}", 1, 32, 128, w_oh, n_queries, BF16, 1.0,
+                    _BASE_SEED + 7 + 7919 * w_oh + 104729 * n_queries)
+
+
 def degenerate_causal() -> Workload:
     """Empty history, window of 4096 rows: the layer reduces to standard causal attention."""
     return sweep_point(0, 4096)
