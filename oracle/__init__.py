@@ -45,6 +45,8 @@ def _load():
         lib.tlin_oracle_window_causal.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, cd, vp, ci, vp, vp]
         lib.tlin_oracle_layer.restype = ci
         lib.tlin_oracle_layer.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cd, ci, vp, ci, vp]
+        lib.tlin_oracle_slide.restype = ci
+        lib.tlin_oracle_slide.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cd, ci, vp, ci, vp]
         lib.tlin_oracle_threads.restype = ci
         _lib = lib
     return _lib
@@ -120,6 +122,23 @@ def layer(Q, Kh, Vh, Kw, Vw, dtype, scale, combine, rows=None):
                                    float(scale), int(combine), _ptr(r), nr, _ptr(O))
     if rc != 0:
         raise RuntimeError(f"tlin_oracle_layer failed ({rc})")
+    return O
+
+
+def slide(Q, Kh, Vh, Kw, Vw, dtype, scale, chunk, combine, rows=None):
+    """Sliding schedule of Section 5.1 over a whole sequence: all tensors [B,H,L,D]; position
+    p = c*chunk + i attends history rows [0, c*chunk) of Kh/Vh unmasked and window rows
+    [c*chunk, p] of Kw/Vw, combined by SUM or JOINT.  Returns O [B,H,R,D] in fp64."""
+    Q, Kh, Vh, Kw, Vw = (_prep(a, dtype) for a in (Q, Kh, Vh, Kw, Vw))
+    B, H, L, D = Q.shape
+    for a in (Kh, Vh, Kw, Vw):
+        assert a.shape == (B, H, L, D)
+    r, nr, R = _rows(rows, L)
+    O = np.empty((B, H, R, D), dtype=np.float64)
+    rc = _load().tlin_oracle_slide(_ptr(Q), _ptr(Kh), _ptr(Vh), _ptr(Kw), _ptr(Vw), dtype, B, H, L, int(chunk), D,
+                                   float(scale), int(combine), _ptr(r), nr, _ptr(O))
+    if rc != 0:
+        raise RuntimeError(f"tlin_oracle_slide failed ({rc})")
     return O
 
 

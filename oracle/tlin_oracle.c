@@ -25,7 +25,9 @@
  * forms (two-key sigmoid, rational-weight worked example, Q=0 mean, N=1, constant V),
  * invariances (key shift, joint row permutation), log-sum-exp against a library routine.
  * The choice of SUM as the combine operator is parity unpinned beyond "sum of two pinned
- * parts".
+ * parts".  The sliding schedule (slide) is pinned by: JOINT with Kh = Kw, Vh = Vw is plain causal
+ * attention over the whole sequence (library routine); SUM is the sum of a library unmasked
+ * attention over the earlier chunks and a library causal attention inside the chunk.
  *
  * Layout: dense [B,H,rows,D], D contiguous.  `rows` (nullable) selects query rows: when
  * given, only those rows are computed for every (b,h) and the outputs have nrows rows.
@@ -219,6 +221,69 @@ int tlin_oracle_layer(const void *Q, const void *Kh, const void *Vh, const void 
                     for (int k = 0; k < D; ++k) o[k] = 0.0;
                     if (N > 0) weighted_values(s, N, m, z, Vh, dtype, (size_t)bh * N * D, D, o);
                     weighted_values(s + N, i + 1, m, z, Vw, dtype, (size_t)bh * W * D, D, o);
+                }
+            }
+        }
+        free(s);
+        free(q);
+        free(t);
+    }
+    return fail ? -2 : 0;
+}
+
+/* The sliding schedule of Section 5.1 over a whole sequence of L rows in one call: the sequence
+ * is cut into chunks of W rows (the last one may be shorter); chunk c is a window whose history
+ * is every earlier chunk, rows [0, c*W), and chunk 0 has an empty history.  Row p = c*W + i
+ * therefore attends history rows [0, c*W) of Kh/Vh without a mask and window rows
+ * [c*W, c*W + i] of Kw/Vw, combined as in tlin_oracle_layer.  All tensors are [B,H,L,D];
+ * `rows` (nullable) selects sequence positions. */
+int tlin_oracle_slide(const void *Q, const void *Kh, const void *Vh, const void *Kw, const void *Vw,
+                      int dtype, int B, int H, int L, int W, int D, double scale, int combine,
+                      const int *rows, int nrows, double *O)
+{
+    if (check(B, H, L, D, rows, nrows) || W < 1 || !Q || !Kh || !Vh || !Kw || !Vw || !O) return -1;
+    if (combine != ORC_SUM && combine != ORC_JOINT) return -1;
+    const int R = rows ? nrows : L;
+    const long total = (long)B * H * R;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * ((size_t)L + 1));
+        double *q = (double *)malloc(sizeof(double) * (size_t)D);
+        double *t = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!s || !q || !t) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 1)
+            for (long u = 0; u < total; ++u) {
+                long bh = u / R;
+                int r = (int)(u % R);
+                int p = rows ? rows[r] : r;
+                int N = (p / W) * W;            /* history rows of this position's chunk */
+                int nw = p - N + 1;             /* visible window rows */
+                size_t base = (size_t)bh * L * D;
+                size_t wbase = base + (size_t)N * D;
+                double *o = O + (size_t)u * D;
+                for (int k = 0; k < D; ++k) q[k] = widen(Q, dtype, base + (size_t)p * D + k);
+                if (combine == ORC_SUM) {
+                    attend(q, Kw, Vw, dtype, wbase, nw, D, scale, s, o);
+                    if (N > 0) {
+                        attend(q, Kh, Vh, dtype, base, N, D, scale, s, t);
+                        for (int k = 0; k < D; ++k) o[k] += t[k];
+                    }
+                } else {
+                    if (N > 0) logits(q, Kh, dtype, base, N, D, scale, s);
+                    logits(q, Kw, dtype, wbase, nw, D, scale, s + N);
+                    int n = N + nw;
+                    double m = row_max(s, n);
+                    double z = 0.0;
+                    for (int j = 0; j < n; ++j) z += exp(s[j] - m);
+                    for (int k = 0; k < D; ++k) o[k] = 0.0;
+                    if (N > 0) weighted_values(s, N, m, z, Vh, dtype, base, D, o);
+                    weighted_values(s + N, nw, m, z, Vw, dtype, wbase, D, o);
                 }
             }
         }

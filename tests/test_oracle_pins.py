@@ -93,6 +93,60 @@ def test_empty_history_layer_is_standard_causal_attention(combine):
     np.testing.assert_allclose(O, ref, rtol=0, atol=1e-13)
 
 
+# ---------------------------------------------------------------- sliding schedule (Section 5.1)
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("L,W", [(37, 8), (64, 16), (50, 50), (23, 40), (41, 1)])
+def test_slide_joint_with_shared_keys_is_causal_attention_over_the_sequence(dtype, L, W):
+    """History = all earlier chunks in full, window = causal inside the chunk: with one key/value
+    tensor for both, one softmax over the two sets is plain causal attention of length L,
+    whatever the chunk size."""
+    B, H, D = 2, 2, 16
+    Q, K, V = (rnd((B, H, L, D), 21, t, 0.8, dtype) for t in (1, 2, 3))
+    scale = 0.29
+    O = oracle.slide(Q, K, V, K, V, dtype, scale, W, oracle.JOINT)
+    q, k, v = (ti.to_f64(x, dtype) for x in (Q, K, V))
+    np.testing.assert_allclose(O, sdpa64(q, k, v, scale, causal=True), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("combine", [oracle.SUM, oracle.JOINT])
+@pytest.mark.parametrize("L,W", [(45, 10), (32, 8), (9, 20)])
+def test_slide_chunks_are_library_attention_per_chunk(combine, L, W):
+    """Distinct history and window projections.  Chunk c against the library: SUM = unmasked
+    attention over rows [0, cW) of Kh/Vh plus causal attention over the chunk's Kw/Vw; JOINT =
+    tail rows of causal attention over [Kh[:cW]; Kw[chunk]].  Chunk 0 has no history."""
+    B, H, D = 1, 3, 8
+    Q, Kh, Vh, Kw, Vw = (rnd((B, H, L, D), 22, t, 0.9) for t in (1, 2, 3, 4, 5))
+    scale = 0.37
+    O = oracle.slide(Q, Kh, Vh, Kw, Vw, ti.F32, scale, W, combine)
+    for c0 in range(0, L, W):
+        c1 = min(c0 + W, L)
+        q, kw, vw = Q[:, :, c0:c1], Kw[:, :, c0:c1], Vw[:, :, c0:c1]
+        if combine == oracle.SUM:
+            ref = sdpa64(q, kw, vw, scale, causal=True)
+            if c0:
+                ref = ref + sdpa64(q, Kh[:, :, :c0], Vh[:, :, :c0], scale)
+        else:
+            qpad = np.concatenate([np.zeros((B, H, c0, D)), q], axis=2)
+            ref = sdpa64(qpad, np.concatenate([Kh[:, :, :c0], kw], 2), np.concatenate([Vh[:, :, :c0], vw], 2),
+                         scale, causal=True)[:, :, c0:]
+        np.testing.assert_allclose(O[:, :, c0:c1], ref, rtol=0, atol=1e-13)
+
+
+def test_slide_row_subset_and_bad_arguments():
+    B, H, L, W, D = 1, 2, 30, 7, 8
+    Q, Kh, Vh, Kw, Vw = (rnd((B, H, L, D), 23, t) for t in (1, 2, 3, 4, 5))
+    full = oracle.slide(Q, Kh, Vh, Kw, Vw, ti.F32, 0.3, W, oracle.SUM)
+    rows = np.array([0, 6, 7, 13, 29], dtype=np.int32)
+    sub = oracle.slide(Q, Kh, Vh, Kw, Vw, ti.F32, 0.3, W, oracle.SUM, rows)
+    np.testing.assert_array_equal(sub, full[:, :, rows])
+    with pytest.raises(RuntimeError):
+        oracle.slide(Q, Kh, Vh, Kw, Vw, ti.F32, 0.3, 0, oracle.SUM)
+    with pytest.raises(RuntimeError):
+        oracle.slide(Q, Kh, Vh, Kw, Vw, ti.F32, 0.3, W, 7)
+    with pytest.raises(RuntimeError):
+        oracle.slide(Q, Kh, Vh, Kw, Vw, ti.F32, 0.3, W, oracle.SUM, np.array([30], dtype=np.int32))
+
+
 # ---------------------------------------------------------------- hand-derived example
 def _golden():
     rows = {}
