@@ -38,11 +38,13 @@ def parse():
     ap.add_argument("--combine", choices=("sum", "joint"), default="sum")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--sweep", action="store_true", help="latency-vs-N sweep instead of the single workload")
-    ap.add_argument("--workload", choices=("config", "decode", "restore"), default="config",
+    ap.add_argument("--workload", choices=("config", "decode", "restore", "slide"), default="config",
                     help="config: --config's layer call (default). decode: the cache-hit step of Section 4.2, "
                          "--W newest rows (default 1) query --N history rows (default 131072) through "
                          "tlin_history_attn. restore: the context path's last layer, --N history rows (default "
-                         "131072) query --W compressed rows (default 256) through tlin_history_attn")
+                         "131072) query --W compressed rows (default 256) through tlin_history_attn. slide: the "
+                         "sliding schedule of Section 5.1 over a sequence of --N rows (default 131072) in chunks of "
+                         "--W rows (default 512) through tlin_slide_layer_attn")
     ap.add_argument("--N", type=int, default=None)
     ap.add_argument("--W", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -119,6 +121,8 @@ def main():
 
     if args.sweep:
         return sweep(args, ti, tl, binding, torch, np, combine)
+    if args.workload == "slide":
+        return slide(args, ti, tl, binding, torch, np, combine)
 
     layer = args.workload == "config"
     if layer:
@@ -222,6 +226,70 @@ MEASURED_TRAFFIC_BYTES = {
 
 def measured_traffic(name):
     return MEASURED_TRAFFIC_BYTES.get(name)
+
+
+def slide(args, ti, tl, binding, torch, np, combine):
+    """One call of tlin_slide_layer_attn over a whole sequence: every chunk of W rows against all
+    earlier chunks plus causal attention inside the chunk."""
+    L, W = args.N or 131072, args.W or 512
+    w = ti.Workload(f"slide_bf16_L{L}_W{W}", 1, 32, 128, L, W, ti.BF16, 1.0, 204077)
+    shape = (w.B, w.H, L, w.D)
+    host = {name: ti.normal(shape, w.dtype, w.seed, tag, w.mul) for name, tag in
+            (("Q", ti.TAG_Q), ("Kh", ti.TAG_KH), ("Vh", ti.TAG_VH), ("Kw", ti.TAG_KW), ("Vw", ti.TAG_VW))}
+    dev = upload(host, w.dtype, ti, torch, np)
+    ws = tl.Workspace()
+
+    def step():
+        return tl.tlin_slide_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], W, combine=combine,
+                                        scale=w.scale, num_splits=args.num_splits, workspace=ws)
+
+    sec = time_steps(step, args.steps, args.warmup, torch)
+    binding.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms, launches = binding.profile_read()
+    binding.profile_enable(False)
+    hist_ms, win_ms, merge_ms = (ms[i] / max(launches[i], 1) for i in range(3))
+    starts = np.arange(0, L, W, dtype=np.float64)
+    lens = np.minimum(W, L - starts)
+    bh = w.B * w.H
+    flops_h = 4.0 * bh * w.D * float(np.sum(lens * starts))
+    flops_w = 4.0 * bh * w.D * float(np.sum(lens * (lens + 1) / 2))
+    kv_bytes = 2.0 * bh * w.D * 2 * float(np.sum(starts))          # every chunk reads its history once
+    tflops = (flops_h + flops_w) / sec / 1e12
+    hist_tflops = flops_h / (hist_ms * 1e-3) / 1e12
+    roof = {"bound": "mfma", "achieved": hist_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": hist_tflops / PEAK_BF16_MFMA_TFLOPS, "kernel": "attn_bf16_kernel (chunk histories)",
+            "kernel_ms": hist_ms, "traffic": None}
+    if W < PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        gbs = kv_bytes / (hist_ms * 1e-3) / 1e9
+        roof.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS})
+    out = {"metric": "sliding schedule over a whole sequence (Section 5.1), bf16: TFLOP/s and tokens/s",
+           "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": w.name, "B": w.B, "H": w.H, "D": w.D, "L_sequence": L, "W_chunk": W,
+                      "combine": args.combine, "step": "tlin_slide_layer_attn = chunk histories + chunk causal + merge"},
+           "tokens_per_s": w.B * L / sec, "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_MFMA_TFLOPS,
+           "kernels_ms": {"history": hist_ms, "window_causal": win_ms, "merge": merge_ms}, "roofline": roof}
+    if not args.no_cpu_baseline:
+        import oracle
+        rng = np.random.default_rng(12345)
+        probe = np.sort(rng.choice(L, size=2, replace=False)).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, W, oracle.SUM, probe)
+        t_probe = time.perf_counter() - t0
+        n = int(max(2, min(L, args.cpu_seconds / max(t_probe, 1e-4) * len(probe))))
+        rows = np.sort(rng.choice(L, size=n, replace=False)).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, W, oracle.SUM, rows)
+        dt = time.perf_counter() - t0
+        keys = float(np.sum(rows + 1))                # history rows + visible window rows of each sampled position
+        out["cpu_baseline"] = {"value": 4.0 * bh * w.D * keys / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
+                               "kind": "oracle", "sample": f"{n} of {L} sequence positions in each of {bh} heads, fp64, "
+                                                           f"{dt:.1f} s", "seconds": dt}
+    print(json.dumps(out), flush=True)
 
 
 def sweep(args, ti, tl, binding, torch, np, combine):

@@ -15,6 +15,8 @@
  *   tlin_window_causal_attn  causal attention inside the window, query i sees keys j <= i
  *                            (Causal attention / "Internal Cohesion", Section 3)
  *   tlin_layer_attn          both for the same W rows, combined (Section 3, generation path)
+ *   tlin_slide_layer_attn    tlin_layer_attn for every chunk of a sequence at once, each chunk's
+ *                            history being all earlier chunks (training schedule, Section 5.1)
  *
  * Conventions common to all entry points
  *   - All tensor pointers and the workspace are DEVICE pointers owned by the caller.  The
@@ -64,7 +66,8 @@ typedef struct {
     int32_t B, H;        /* batch, heads: B*H independent problems, each >= 1 */
     int32_t W;           /* window (query) rows, >= 1 */
     int32_t N;           /* history rows; >= 1 for tlin_history_attn, >= 0 for tlin_layer_attn,
-                            ignored by tlin_window_causal_attn */
+                            ignored by tlin_window_causal_attn; sequence rows (>= 1) for
+                            tlin_slide_layer_attn, whose chunk length is W */
     int32_t D;           /* head dimension: 64 or 128 */
     int32_t in_dtype;    /* tlin_dtype of Q, K, V */
     int32_t out_dtype;   /* tlin_dtype of O */
@@ -110,6 +113,23 @@ tlin_status tlin_window_causal_attn(const tlin_params *p, const void *Q_win, con
 tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void *K_hist,
                             const void *V_hist, const void *K_win, const void *V_win, void *O,
                             void *ws, size_t ws_bytes, void *stream);
+
+/* The sliding schedule of Section 5.1 over a whole sequence in one call: the sequence of
+ * p->N rows is cut into chunks of p->W rows (the last one may be shorter); chunk c is a window
+ * whose history is every earlier chunk, so row c*W + i attends rows [0, c*W) of K_hist/V_hist
+ * without a mask and rows [c*W, c*W + i] of K_win/V_win causally, joined per p->combine.
+ * Chunk 0 has an empty history.  Equivalent to one tlin_layer_attn call per chunk; done as
+ * three launches for all chunks together, the longest histories scheduled first.
+ *   Q, K_hist, V_hist, K_win, V_win: [B,H,N,D] in in_dtype; O [B,H,N,D] in out_dtype.
+ *   K_hist/V_hist may be the same buffers as K_win/V_win (one projection for both roles).
+ *   p->num_splits: partitions per chunk history; 0 = choose automatically.
+ *   ws: at least tlin_slide_workspace_bytes(p) bytes, 256-byte aligned (two or more fp32
+ *       partials per output row: size it before choosing very long sequences).
+ * tlin_slide_workspace_bytes returns 0 for invalid parameters. */
+size_t tlin_slide_workspace_bytes(const tlin_params *p);
+tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const void *K_hist,
+                                  const void *V_hist, const void *K_win, const void *V_win, void *O,
+                                  void *ws, size_t ws_bytes, void *stream);
 
 /* Measurement aid (not part of the attention path).  While enabled, every kernel the library
  * launches is bracketed by a pair of HIP events recorded on the launch stream.

@@ -10,7 +10,7 @@ from __future__ import annotations
 from . import binding
 from .binding import (TLIN_BF16, TLIN_COMBINE_JOINT, TLIN_COMBINE_SUM, TLIN_F32, TlinError, TlinParams)
 
-__all__ = ["tlin_history_attn", "tlin_window_causal_attn", "tlin_layer_attn", "Workspace", "params_for",
+__all__ = ["tlin_history_attn", "tlin_window_causal_attn", "tlin_layer_attn", "tlin_slide_layer_attn", "Workspace", "params_for",
            "TLIN_F32", "TLIN_BF16", "TLIN_COMBINE_SUM", "TLIN_COMBINE_JOINT", "TlinError", "TlinParams",
            "binding"]
 
@@ -123,4 +123,26 @@ def tlin_layer_attn(q_win, k_hist, v_hist, k_win, v_win, *, combine=TLIN_COMBINE
                                 v_hist.data_ptr() if n else None, k_win.data_ptr(), v_win.data_ptr(),
                                 o.data_ptr(), ws or None, nb, _stream(q_win))
     binding._check(st, "tlin_layer_attn")
+    return o
+
+
+def tlin_slide_layer_attn(q, k_hist, v_hist, k_win, v_win, chunk, *, combine=TLIN_COMBINE_SUM, scale=None,
+                          out_dtype=None, num_splits=0, workspace: Workspace | None = None):
+    """tlin_layer_attn for every chunk of `chunk` rows of a whole sequence [B,H,L,D] at once;
+    the history of a chunk is every earlier chunk (k_hist/v_hist rows before it)."""
+    _require_gpu(q, k_hist, v_hist, k_win, v_win)
+    B, H, L, D = q.shape
+    for t in (k_hist, v_hist, k_win, v_win):
+        if tuple(t.shape) != (B, H, L, D):
+            raise ValueError("all tensors of the sliding schedule are [B,H,L,D]")
+    o = _out(q, out_dtype)
+    code = _dtype_code(q)
+    oc = TLIN_F32 if o.dtype == _torch().float32 else TLIN_BF16
+    p = binding.make_params(B, H, int(chunk), L, D, code, oc, (D ** -0.5) if scale is None else scale, num_splits,
+                            combine, q_stride=_strides(q), kh_stride=_strides(k_hist), vh_stride=_strides(v_hist),
+                            kw_stride=_strides(k_win), vw_stride=_strides(v_win), o_stride=_strides(o))
+    ws, nb = (workspace or _default_ws).get(binding.slide_workspace_bytes(p), q.device)
+    st = binding.slide_layer_attn_raw(p, q.data_ptr(), k_hist.data_ptr(), v_hist.data_ptr(), k_win.data_ptr(),
+                                      v_win.data_ptr(), o.data_ptr(), ws or None, nb, _stream(q))
+    binding._check(st, "tlin_slide_layer_attn")
     return o

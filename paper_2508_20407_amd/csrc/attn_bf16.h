@@ -104,26 +104,27 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
 
     const int L = xcd_remap(blockIdx.x, gridDim.x);
     const int qstep = RESIDENT ? a.q_groups : a.nqb;   // workgroups along the query axis of one head
-    int qb = L % qstep;
-    const int rest = L / qstep;
-    const int split = rest % a.nsplit;
-    const int bh = rest / a.nsplit;
+    const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, qstep);
+    if (pr.skip) return;                               // uniform over the workgroup
+    int qb = pr.qb;
+    const int split = pr.split, bh = pr.bh;
     const int b = bh / a.H, hd = bh % a.H;
+    const int Wq = pr.W, NK = pr.NK;                   // query and key rows of this problem
 
     int t0, t1;
     if (CAUSAL) {
         t0 = 0;
-        const int kend = min(a.NK, qb * BM + BM);
+        const int kend = min(NK, qb * BM + BM);
         t1 = (kend + BN - 1) / BN;
     } else {
-        t0 = split * a.tiles_per_split;
-        t1 = min(t0 + a.tiles_per_split, (a.NK + BN - 1) / BN);
+        t0 = split * pr.tps;
+        t1 = min(t0 + pr.tps, (NK + BN - 1) / BN);
     }
 
-    const __bf16 *Qg = (const __bf16 *)a.Q + (int64_t)b * a.q_sb + (int64_t)hd * a.q_sh;
-    const char *Kg = (const char *)((const __bf16 *)a.K + (int64_t)b * a.k_sb + (int64_t)hd * a.k_sh);
-    const char *Vg = (const char *)((const __bf16 *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh);
     const int64_t k_rb = a.k_sr * 2, v_rb = a.v_sr * 2;
+    const __bf16 *Qg = (const __bf16 *)a.Q + (int64_t)b * a.q_sb + (int64_t)hd * a.q_sh + pr.qrow_off * a.q_sr;
+    const char *Kg = (const char *)((const __bf16 *)a.K + (int64_t)b * a.k_sb + (int64_t)hd * a.k_sh) + pr.krow_off * k_rb;
+    const char *Vg = (const char *)((const __bf16 *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh) + pr.krow_off * v_rb;
 
     int qrow0 = qb * BM + wave * (QB * 32);
     bf16x8 qf[QB][DS];
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     auto load_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int qi = 0; qi < QB; ++qi) {
-            const int r = min(qrow0 + qi * 32 + j, a.W - 1);
+            const int r = min(qrow0 + qi * 32 + j, Wq - 1);
             const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
 #pragma unroll
             for (int s = 0; s < DS; ++s) qf[qi][s] = *(const bf16x8 *)(qp + 16 * s);
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
         const int key0 = t * BN;
         const unsigned kdst = __builtin_amdgcn_readfirstlane(lds_offset(Ks) + stage * TILE_B + wave * (NDMA * 1024));
         const unsigned vdst = kdst + NSTAGE * TILE_B;
-        if (key0 + BN <= a.NK) {
+        if (key0 + BN <= NK) {
             const char *kt = Kg + key0 * k_rb, *vt = Vg + key0 * v_rb;
 #pragma unroll
             for (int i = 0; i < NDMA; ++i) {
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
             // ragged last tile: rows past the end repeat the last row (their scores are masked)
 #pragma unroll
             for (int i = 0; i < NDMA; ++i) {
-                const int64_t back = max(key0 + drow[i] - (a.NK - 1), 0);
+                const int64_t back = max(key0 + drow[i] - (NK - 1), 0);
                 direct_load_1k(Kg + (key0 - back) * k_rb + koff[i], kdst + i * 1024);
                 direct_load_1k(Vg + (key0 - back) * v_rb + voff[i], vdst + i * 1024);
             }
@@ -234,13 +235,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
         }
 
         // mask: keys past the end of the tensor, and (causal) keys after the query row
-        const bool ragged = key0 + BN > a.NK;
+        const bool ragged = key0 + BN > NK;
         const bool diag = CAUSAL && (key0 + BN - 1 > qrow0);
         if (ragged || diag) {
 #pragma unroll
             for (int qi = 0; qi < QB; ++qi) {
                 const int row = qrow0 + qi * 32 + j;
-                const int lim = CAUSAL ? min(row, a.NK - 1) : a.NK - 1;   // last visible key
+                const int lim = CAUSAL ? min(row, NK - 1) : NK - 1;   // last visible key
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -344,7 +345,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
             const int nrow0 = (qb + qstep) * BM + wave * (QB * 32);
 #pragma unroll
             for (int qi = 0; qi < QB; ++qi) {
-                const int r = min(nrow0 + qi * 32 + j, a.W - 1);
+                const int r = min(nrow0 + qi * 32 + j, Wq - 1);
                 const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
 #pragma unroll
                 for (int s = 0; s < DS; ++s) qn[qi][s] = *(const bf16x8 *)(qp + 16 * s);
@@ -373,10 +374,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     for (int qi = 0; qi < QB; ++qi) {
         const float lt = xhalf_sum(l[qi]);
         const int row = qrow0 + qi * 32 + j;
-        if (row >= a.W) continue;
+        if (row >= Wq) continue;
         if (a.direct) {
             const float inv = 1.0f / lt;
-            const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)row * a.o_sr;
+            const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (pr.qrow_off + row) * a.o_sr;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
                 }
             if (a.lse && h == 0) a.lse[(int64_t)bh * a.W + row] = m[qi] * a.scale + logf(lt);
         } else {
-            const int64_t slot = (int64_t)bh * a.nparts + a.part0 + (CAUSAL ? 0 : split);
+            const int64_t slot = pr.slot + a.part0 + (CAUSAL ? 0 : split);
             float *op = a.Opart + (slot * a.W + row) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)

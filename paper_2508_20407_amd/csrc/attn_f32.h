@@ -30,29 +30,29 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
 
     const int tid = threadIdx.x;
     const int L = xcd_remap(blockIdx.x, gridDim.x);
-    const int qb = L % a.nqb;
-    const int rest = L / a.nqb;
-    const int split = rest % a.nsplit;
-    const int bh = rest / a.nsplit;
+    const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, a.nqb);
+    if (pr.skip) return;                 // uniform over the workgroup
+    const int qb = pr.qb, split = pr.split, bh = pr.bh;
     const int b = bh / a.H, hd = bh % a.H;
     const int qrow0 = qb * BM;
+    const int Wq = pr.W, NK = pr.NK;     // query and key rows of this problem
 
     int t0, t1;
     if (CAUSAL) {
         t0 = 0;
-        t1 = (min(a.NK, qrow0 + BM) + BN - 1) / BN;
+        t1 = (min(NK, qrow0 + BM) + BN - 1) / BN;
     } else {
-        t0 = split * a.tiles_per_split;
-        t1 = min(t0 + a.tiles_per_split, (a.NK + BN - 1) / BN);
+        t0 = split * pr.tps;
+        t1 = min(t0 + pr.tps, (NK + BN - 1) / BN);
     }
 
-    const float *Qg = (const float *)a.Q + (int64_t)b * a.q_sb + (int64_t)hd * a.q_sh;
-    const float *Kg = (const float *)a.K + (int64_t)b * a.k_sb + (int64_t)hd * a.k_sh;
-    const float *Vg = (const float *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh;
+    const float *Qg = (const float *)a.Q + (int64_t)b * a.q_sb + (int64_t)hd * a.q_sh + pr.qrow_off * a.q_sr;
+    const float *Kg = (const float *)a.K + (int64_t)b * a.k_sb + (int64_t)hd * a.k_sh + pr.krow_off * a.k_sr;
+    const float *Vg = (const float *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh + pr.krow_off * a.v_sr;
 
     for (int i = tid; i < BM * (D / 4); i += NT) {
         const int r = i / (D / 4), c4 = i % (D / 4);
-        const int gr = min(qrow0 + r, a.W - 1);
+        const int gr = min(qrow0 + r, Wq - 1);
         *(f32x4 *)(Qs + r * LDQ + 4 * c4) = *(const f32x4 *)(Qg + (int64_t)gr * a.q_sr + 4 * c4);
     }
 
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
         __syncthreads();   // previous tile fully consumed
         for (int i = tid; i < BN * (D / 4); i += NT) {
             const int r = i / (D / 4), c4 = i % (D / 4);
-            const int gr = min(key0 + r, a.NK - 1);
+            const int gr = min(key0 + r, NK - 1);
             *(f32x4 *)(Ks + r * LDQ + 4 * c4) = *(const f32x4 *)(Kg + (int64_t)gr * a.k_sr + 4 * c4);
             *(f32x4 *)(Vs + r * D + 4 * c4) = *(const f32x4 *)(Vg + (int64_t)gr * a.v_sr + 4 * c4);
         }
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int row = qrow0 + 2 * ty + r;
-            const int lim = CAUSAL ? min(row, a.NK - 1) : a.NK - 1;
+            const int lim = CAUSAL ? min(row, NK - 1) : NK - 1;
 #pragma unroll
             for (int c = 0; c < SC; ++c) {
                 const int key = key0 + tx + 16 * c;
@@ -173,11 +173,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const int lr = 2 * ty + r, row = qrow0 + lr;
-        if (row >= a.W) continue;
+        if (row >= Wq) continue;
         const float mr = m_s[lr], lt = l_s[lr];
         if (a.direct) {
             const float inv = 1.0f / lt;
-            const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)row * a.o_sr;
+            const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (pr.qrow_off + row) * a.o_sr;
 #pragma unroll
             for (int c = 0; c < CPT; ++c) {
                 const int d = 4 * tx + 64 * c;
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
             // m is in base-2 units (c * raw); natural-log LSE = m * ln 2 + ln l
             if (a.lse && tx == 0) a.lse[(int64_t)bh * a.W + row] = mr * 0.6931471805599453f + logf(lt);
         } else {
-            const int64_t slot = (int64_t)bh * a.nparts + a.part0 + (CAUSAL ? 0 : split);
+            const int64_t slot = pr.slot + a.part0 + (CAUSAL ? 0 : split);
             float *op = a.Opart + (slot * a.W + row) * D;
 #pragma unroll
             for (int c = 0; c < CPT; ++c) *(f32x4 *)(op + 4 * tx + 64 * c) = oacc[r][c];

@@ -29,6 +29,12 @@ struct AttnArgs {
     int32_t NK;                 // key rows
     int32_t nqb;                // query blocks per head
     int32_t q_groups;           // resident variant: workgroups per head; each takes blocks g, g+q_groups, ...
+    // Sliding schedule (nchunks > 0): Q, K, V hold seq_rows rows per head; chunk c (W rows, the
+    // last one shorter) queries rows [0, c*W) of K/V (history launch) or its own rows causally
+    // (window launch).  The block index then also enumerates chunks, longest history first, and
+    // partial slots are numbered (bh * nchunks + c) * nparts + part.
+    int32_t nchunks;
+    int32_t seq_rows;
     int32_t nsplit;             // key partitions (1 for the causal kernel)
     int32_t tiles_per_split;    // key tiles (of 64 rows) per partition
     int32_t nparts;             // partial slots per (b,h) in the workspace
@@ -56,7 +62,9 @@ struct MergeArgs {
     int64_t o_sb, o_sh, o_sr;
     float *lse;                 // nullable
     int32_t out_bf16;
-    int32_t total_rows;         // BH * W
+    int32_t total_rows;         // BH * W (sliding schedule: BH * seq_rows)
+    int32_t nchunks;            // sliding schedule: chunks of W rows per head (0 otherwise); chunk 0 has no history
+    int32_t seq_rows;           // sliding schedule: output rows per head
 };
 
 // Workgroups are dispatched round-robin over the 8 XCDs, each with a private L2.  Map the
@@ -67,6 +75,58 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks)
     const int per = nblocks / kNumXCD, rem = nblocks % kNumXCD;
     const int xcd = bid % kNumXCD, slot = bid / kNumXCD;
     return xcd * per + (xcd < rem ? xcd : rem) + slot;
+}
+
+// What one workgroup works on, after the sliding-schedule indirection has been resolved.
+struct Problem {
+    int bh, qb, split;
+    int W;            // query rows of this problem (chunk length, or the whole window)
+    int NK;           // key rows
+    int64_t qrow_off; // first query row inside the head's Q (and output) rows
+    int64_t krow_off; // first key row inside the head's K/V rows
+    int64_t slot;     // first partial slot of this (head, chunk)
+    int tps;          // key tiles per partition
+    bool skip;        // nothing to do (rows past a short last chunk, or an empty history)
+};
+
+// Decode the logical block index.  BM: query rows per workgroup, BN: keys per tile.
+template <int BM, int BN, bool CAUSAL>
+__device__ __forceinline__ Problem decode_problem(const AttnArgs &a, int L, int qstep)
+{
+    Problem p;
+    p.qb = L % qstep;
+    int rest = L / qstep;
+    p.split = rest % a.nsplit;
+    rest /= a.nsplit;
+    if (a.nchunks == 0) {
+        p.bh = rest;
+        p.W = a.W;
+        p.NK = a.NK;
+        p.qrow_off = 0;
+        p.krow_off = 0;
+        p.slot = (int64_t)p.bh * a.nparts;
+        p.tps = a.tiles_per_split;
+        p.skip = false;
+        return p;
+    }
+    const int c = a.nchunks - 1 - rest % a.nchunks;   // longest histories first
+    p.bh = rest / a.nchunks;
+    const int row0 = c * a.W;
+    p.W = min(a.W, a.seq_rows - row0);
+    p.qrow_off = row0;
+    p.slot = ((int64_t)p.bh * a.nchunks + c) * a.nparts;
+    if (CAUSAL) {
+        p.NK = p.W;
+        p.krow_off = row0;
+        p.tps = a.tiles_per_split;
+    } else {
+        p.NK = row0;
+        p.krow_off = 0;
+        const int tiles = (row0 + BN - 1) / BN;
+        p.tps = (tiles + a.nsplit - 1) / a.nsplit;
+    }
+    p.skip = p.qb * BM >= p.W || p.NK == 0;
+    return p;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -22,20 +22,29 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a)
     const int64_t grow = (int64_t)blockIdx.x * RPB + tid / TPR;   // flat row index over (b,h,row)
     if (grow >= a.total_rows) return;
     const int c4 = (tid % TPR) * 4;
-    const int bh = (int)(grow / a.W), row = (int)(grow % a.W);
+    // Sliding schedule: the row belongs to chunk orow / W of its head, the partials of a chunk sit
+    // in its own group of slots, and chunk 0 has no history partials.
+    const int rows_per_head = a.nchunks ? a.seq_rows : a.W;
+    const int bh = (int)(grow / rows_per_head), orow = (int)(grow % rows_per_head);
+    const int chunk = a.nchunks ? orow / a.W : 0;
+    const int row = orow - chunk * a.W;
     const int b = bh / a.H, hd = bh % a.H;
-    const int64_t slot0 = (int64_t)bh * a.nparts;
+    const int64_t slot0 = ((int64_t)bh * (a.nchunks ? a.nchunks : 1) + chunk) * a.nparts;
+    const int nhist = (a.nchunks && chunk == 0) ? 0 : a.nhist;
+    const int64_t wslot = slot0 + a.nhist;             // the window partial's slot
 
-    const int njoint = a.nhist + ((a.has_window && a.joint) ? 1 : 0);
+    const int njoint = nhist + ((a.has_window && a.joint) ? 1 : 0);
     f32x4 o = {0.f, 0.f, 0.f, 0.f};
     float lse2 = -INFINITY;
     if (njoint > 0) {
         float M = -INFINITY;
-        for (int s = 0; s < njoint; ++s) M = fmaxf(M, a.Mpart[(slot0 + s) * a.W + row]);
+        // joint slots: the history partials, then (JOINT) the window partial
+        auto slot_of = [&](int s) { return s < nhist ? slot0 + s : wslot; };
+        for (int s = 0; s < njoint; ++s) M = fmaxf(M, a.Mpart[slot_of(s) * a.W + row]);
         float den = 0.f;
         f32x4 num = {0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < njoint; ++s) {
-            const int64_t idx = (slot0 + s) * a.W + row;
+            const int64_t idx = slot_of(s) * a.W + row;
             const float w = exp2f(a.Mpart[idx] - M);
             den += w * a.Lpart[idx];
             num += w * *(const f32x4 *)(a.Opart + idx * D + c4);
@@ -44,11 +53,11 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a)
         lse2 = M + log2f(den);
     }
     if (a.has_window && !a.joint) {
-        const int64_t idx = (slot0 + a.nhist) * a.W + row;
+        const int64_t idx = wslot * a.W + row;
         o += *(const f32x4 *)(a.Opart + idx * D + c4) * (1.0f / a.Lpart[idx]);
     }
 
-    const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)row * a.o_sr + c4;
+    const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)orow * a.o_sr + c4;
     if (a.out_bf16) {
         bf16x4 ob;
 #pragma unroll

@@ -149,6 +149,41 @@ Plan plan_history(const tlin_params *p)
     return {(ntiles + tps - 1) / tps, tps};   // no partition is empty
 }
 
+// Sliding schedule: chunks of W rows over a sequence of N rows; every chunk's history is cut into
+// the same number of partitions (their length grows with the chunk index).
+struct SlidePlan { int nchunks, nsplit, nparts; };
+
+SlidePlan plan_slide(const tlin_params *p)
+{
+    const int nchunks = (p->N + p->W - 1) / p->W;
+    const int bn = key_tile(p->in_dtype, p->D);
+    const int qblk = query_block(p->in_dtype, p->W);
+    const int nqb = (p->W + qblk - 1) / qblk;
+    int want;
+    if (p->num_splits > 0) {
+        want = p->num_splits;
+    } else {
+        // With many chunks the work items (head, chunk, query block) already outnumber the compute
+        // units several times and the long ones start first; split only short sequences.
+        const int64_t items = (int64_t)p->B * p->H * nqb * (nchunks > 1 ? nchunks - 1 : 1);
+        const int64_t target = 2 * (int64_t)resident_wgs(p->in_dtype, p->W);
+        want = (int)((target + items - 1) / items);
+    }
+    // at least 4 tiles per partition in the longest history
+    const int max_tiles = (int)(((int64_t)(nchunks - 1) * p->W + bn - 1) / bn);
+    const int cap = max_tiles / 4 > 1 ? max_tiles / 4 : 1;
+    if (want > cap) want = cap;
+    if (want > 64) want = 64;
+    if (want < 1) want = 1;
+    return {nchunks, want, want + 1};
+}
+
+size_t slide_ws_bytes(const tlin_params *p, const SlidePlan &pl)
+{
+    const size_t rows = (size_t)p->B * p->H * pl.nchunks * pl.nparts * p->W;
+    return rows * p->D * sizeof(float) + 2 * rows * sizeof(float);
+}
+
 size_t ws_bytes_for(const tlin_params *p, int nparts)
 {
     const size_t rows = (size_t)p->B * p->H * nparts * p->W;
@@ -224,7 +259,7 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
         if (rc != TLIN_OK) return rc;
         return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
     }
-    const int64_t grid64 = (int64_t)p->B * p->H * a.nqb * a.nsplit;
+    const int64_t grid64 = (int64_t)p->B * p->H * a.nqb * a.nsplit * (a.nchunks ? a.nchunks : 1);
     if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     const int grid = (int)grid64;
     LaunchTimer timer(causal ? KC_WINDOW : KC_HISTORY, st);
@@ -251,7 +286,7 @@ tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
     m.H = p->H;
     m.W = p->W;
     m.out_bf16 = p->out_dtype == TLIN_BF16;
-    const int64_t total = (int64_t)p->B * p->H * p->W;
+    const int64_t total = (int64_t)p->B * p->H * (m.nchunks ? m.seq_rows : p->W);
     if (total > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     m.total_rows = (int)total;
     const int rpb = 256 / (p->D / 4);
@@ -404,6 +439,60 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
     if ((st = launch_attn(p, true, aw, hs))) return st;
 
     return launch_merge(p, merge_args(p, w, nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr), hs);
+}
+
+size_t tlin_slide_workspace_bytes(const tlin_params *p)
+{
+    if (check_common(p, true, false) != TLIN_OK) return 0;
+    const SlidePlan pl = plan_slide(p);
+    return slide_ws_bytes(p, pl);
+}
+
+tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const void *K_hist, const void *V_hist,
+                                  const void *K_win, const void *V_win, void *O, void *ws, size_t ws_bytes,
+                                  void *stream)
+{
+    tlin_status st = check_common(p, true, false);
+    if (st) return st;
+    if (p->combine != TLIN_COMBINE_SUM && p->combine != TLIN_COMBINE_JOINT) return TLIN_ERR_INVALID_ARG;
+    if (!Q || !K_hist || !V_hist || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
+    if (!aligned(Q, 16) || !aligned(K_hist, 16) || !aligned(V_hist, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) ||
+        !aligned(O, 16))
+        return TLIN_ERR_INVALID_ARG;
+    hipStream_t hs = (hipStream_t)stream;
+    const SlidePlan pl = plan_slide(p);
+    if ((int64_t)p->B * p->H * pl.nchunks * pl.nparts > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
+    if ((st = check_ws(ws, ws_bytes, slide_ws_bytes(p, pl)))) return st;
+    // partial slots: (b*H + h, chunk, part), W rows each
+    const size_t rows = (size_t)p->B * p->H * pl.nchunks * pl.nparts * p->W;
+    float *base = (float *)ws;
+    const Workspace w = {base, base + rows * p->D, base + rows * p->D + rows};
+
+    // every tensor has p->N rows per head
+    const Strides q = resolve(p->q_stride, p->H, p->N, p->D);
+    const Strides o = resolve(p->o_stride, p->H, p->N, p->D);
+    auto args = [&](const void *K, const void *V, const int64_t ks[3], const int64_t vs[3]) {
+        AttnArgs a = base_args(p, Q, K, V, ks, vs, p->N);
+        a.q_sb = q.b; a.q_sh = q.h; a.q_sr = q.r;
+        a.nchunks = pl.nchunks;
+        a.seq_rows = p->N;
+        return a;
+    };
+    if (pl.nchunks > 1) {
+        AttnArgs ah = args(K_hist, V_hist, p->kh_stride, p->vh_stride);
+        ah.nsplit = pl.nsplit;
+        set_partial(ah, w, pl.nparts, 0);
+        if ((st = launch_attn(p, false, ah, hs))) return st;
+    }
+    AttnArgs aw = args(K_win, V_win, p->kw_stride, p->vw_stride);
+    set_partial(aw, w, pl.nparts, pl.nsplit);
+    if ((st = launch_attn(p, true, aw, hs))) return st;
+
+    MergeArgs m = merge_args(p, w, pl.nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr);
+    m.o_sb = o.b; m.o_sh = o.h; m.o_sr = o.r;
+    m.nchunks = pl.nchunks;
+    m.seq_rows = p->N;
+    return launch_merge(p, m, hs);
 }
 
 tlin_status tlin_profile_enable(int32_t enable)

@@ -94,6 +94,29 @@ def test_null_and_misaligned_pointers_and_workspace():
     assert b.layer_attn_raw(P(N=-1), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
 
 
+def test_slide_planning_and_argument_checks():
+    # 256 chunks of 512 rows, 32 heads: plenty of work items, so one partition per chunk history
+    # plus the window partial = 2 fp32 partial slots per output row
+    p = P(B=1, H=32, W=512, N=131072, D=128)
+    rows = 32 * 256 * 2 * 512
+    assert b.slide_workspace_bytes(p) == rows * 128 * 4 + 2 * rows * 4
+    # a short sequence is split further; the ragged last chunk still gets whole slots
+    small = P(B=1, H=1, W=128, N=1000, D=64)
+    need = b.slide_workspace_bytes(small)
+    per_slot = 128 * 64 * 4 + 2 * 128 * 4
+    assert need % (8 * per_slot) == 0 and need // (8 * per_slot) >= 2
+    forced = P(B=1, H=1, W=128, N=1000, D=64, num_splits=3)
+    assert b.slide_workspace_bytes(forced) == 8 * 4 * per_slot
+    assert b.slide_workspace_bytes(P(N=0)) == 0 and b.slide_workspace_bytes(P(D=96)) == 0
+    big = 1 << 40
+    assert b.slide_layer_attn_raw(P(N=0), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.slide_layer_attn_raw(P(combine=2), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.slide_layer_attn_raw(p, A, A, None, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.slide_layer_attn_raw(p, A, A, A, A, A + 4, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.slide_layer_attn_raw(p, A, A, A, A, A, A, None, 0, None) == b.TLIN_ERR_WORKSPACE
+    assert b.slide_layer_attn_raw(p, A, A, A, A, A, A, A, 1 << 20, None) == b.TLIN_ERR_WORKSPACE
+
+
 def test_binding_fails_loudly_when_library_is_missing(monkeypatch):
     monkeypatch.setattr(b, "_lib", None)
     monkeypatch.setattr(b, "LIB_PATH", "/nonexistent/libtlinattn.so")

@@ -160,6 +160,63 @@ def test_restoration_shape_keys_resident_in_lds_every_row(D, n_queries, w_oh):
     assert_close(o32, ro, w.dtype, w.name + " f32 out")
 
 
+# ---------------------------------------------------------------- sliding schedule over a whole sequence
+def run_slide(w: ti.Workload, chunk, rows=None, num_splits=0, shared=False):
+    """tlin_slide_layer_attn against the oracle; w.N is the sequence length (w.W unused)."""
+    L = w.N
+    shape = (w.B, w.H, L, w.D)
+    host = {name: ti.normal(shape, w.dtype, w.seed, tag, w.mul) for name, tag in
+            (("Q", ti.TAG_Q), ("Kh", ti.TAG_KH), ("Vh", ti.TAG_VH), ("Kw", ti.TAG_KW), ("Vw", ti.TAG_VW))}
+    if shared:
+        host["Kw"], host["Vw"] = host["Kh"], host["Vh"]
+    dev = upload(host, w.dtype)
+    if shared:
+        dev["Kw"], dev["Vw"] = dev["Kh"], dev["Vh"]
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_slide_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], chunk, combine=mode,
+                                     scale=w.scale, num_splits=num_splits)
+        ro = oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, chunk, omode,
+                          rows)
+        g = o if rows is None else o[:, :, torch.from_numpy(rows).long().cuda()]
+        assert_close(g, ro, w.dtype, f"{w.name} slide chunk {chunk} mode {mode}")
+    return o
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("L,chunk", [(1000, 128), (1024, 256), (777, 64), (300, 512), (130, 1), (2100, 300), (4096, 512)])
+def test_slide_every_row(dtype, D, L, chunk):
+    w = ti.Workload(f"slide_{dtype}_{D}_{L}_{chunk}", 2, 2, D, L, chunk, dtype, 1.0, 4242 + L + chunk)
+    run_slide(w, chunk)
+
+
+@pytest.mark.parametrize("num_splits", [1, 3, 7])
+def test_slide_partition_count_does_not_change_the_result_class(num_splits):
+    w = ti.Workload("slide_splits", 1, 3, 128, 3000, 256, ti.BF16, 1.0, 5151)
+    run_slide(w, 256, num_splits=num_splits)
+
+
+def test_slide_joint_with_shared_keys_is_causal_attention():
+    """One K/V tensor in both roles and one softmax: the sliding schedule is plain causal
+    attention over the sequence; compared with the library's own window causal kernel run on
+    the whole sequence as one window, and with the oracle."""
+    w = ti.Workload("slide_shared", 1, 4, 128, 2048, 256, ti.BF16, 1.0, 6161)
+    o = run_slide(w, 256, shared=True)       # returns the JOINT result
+    host = {name: ti.normal((w.B, w.H, w.N, w.D), w.dtype, w.seed, tag, w.mul) for name, tag in
+            (("Q", ti.TAG_Q), ("K", ti.TAG_KH), ("V", ti.TAG_VH))}
+    dev = upload(host, w.dtype)
+    ref = tl.tlin_window_causal_attn(dev["Q"], dev["K"], dev["V"], scale=w.scale)
+    assert_close(o, to_host64(ref), w.dtype, "slide JOINT vs one causal window")
+
+
+def test_slide_full_size_sampled_rows():
+    """The sequence length of the largest fixed workload cut into its window length: 256 chunks
+    of 512 rows, 32 heads, in the launch configuration the bench times."""
+    w = ti.Workload("slide_bf16_L131072_W512", 1, 32, 128, 131072, 512, ti.BF16, 1.0, 7171)
+    rows = np.array([0, 511, 512, 1000, 65535, 65536, 100000, 131071 - 512, 131071], dtype=np.int32)
+    run_slide(w, 512, rows=rows)
+
+
 # ---------------------------------------------------------------- shapes, tails, degenerate cases
 @pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
 @pytest.mark.parametrize("D", [64, 128])
