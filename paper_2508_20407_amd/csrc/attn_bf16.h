@@ -77,7 +77,8 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // its waves drift apart and one wave's matrix work overlaps another's softmax arithmetic.  Used
 // where the query side is the long one.
 template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
+void attn_bf16_kernel(const AttnArgs a)
 {
     static_assert(!(RESIDENT && CAUSAL), "the resident variant is for unmasked attention");
     constexpr int BN = 64;                 // keys per tile
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
         koff[i] = drow[i] * k_rb + (((lane % CPR) ^ Swz<D>::k(drow[i])) << 4);
         voff[i] = drow[i] * v_rb + (((lane % CPR) ^ Swz<D>::v(drow[i])) << 4);
     }
-    auto issue = [&](int t, int stage) {
+    auto issue = [&](int t, int stage) __attribute__((always_inline)) {
         const int key0 = t * BN;
         const unsigned kdst = __builtin_amdgcn_readfirstlane(lds_offset(Ks) + stage * TILE_B + wave * (NDMA * 1024));
         const unsigned vdst = kdst + NSTAGE * TILE_B;
@@ -202,26 +203,50 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     bf16x8 pb[QB][2][2];   // softmax weights of the current tile, B-operand order
 
     // ---- scores and online softmax of one tile: S^T = K Q^T, mask, update m/l, weights -> pb
-    auto scores_softmax = [&](const char *Kt, int key0) {
-        // The K fragments of KPF 32-key blocks are requested from LDS before the first product
-        // so that the reads overlap the matrix-core work instead of serialising with it.
+    auto scores_softmax = [&](const char *Kt, int key0) __attribute__((always_inline)) {
         f32x16 sacc[QB][2];
-        constexpr int KPF = (QB == 1 && !(CAUSAL && D == 128)) ? 2 : 1;
+        // Register budget decides how the K fragments come from LDS.  AHEAD: all fragments of the
+        // tile are requested back to back before the first product.  Otherwise one 32-key block
+        // at a time, under the compiler's own waits.
+        constexpr bool AHEAD = QB == 1 && !(CAUSAL && D == 128);
+        if constexpr (AHEAD) {
+            // Requests go out in the order the products consume them (contraction step outer,
+            // 32-key block inner), and every product waits only until its own operand has
+            // arrived: LDS reads complete in order, so operand number i of n is there once at most
+            // n-1-i reads are outstanding.  The reads and the waits are written as assembly because
+            // the compiler otherwise waits for all of them before the first product.  (Outstanding
+            // reads the compiler adds on its own can only make a wait longer, never too short.)
+            bf16x8 kf[2][DS];
+            const unsigned kaddr = lds_offset(Kt) + j * ROWB;
+            const int ksw = Swz<D>::k(j);                 // same for keys j and j + 32
 #pragma unroll
-        for (int kb0 = 0; kb0 < 2; kb0 += KPF) {
-            bf16x8 kf[KPF][DS];
+            for (int s = 0; s < DS; ++s) {
+                const unsigned addr = kaddr + (((2 * s + h) ^ ksw) << 4);
+                asm volatile("ds_read_b128 %0, %1" : "=v"(kf[0][s]) : "v"(addr));
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[1][s]) : "v"(addr), "n"(32 * ROWB));
+            }
 #pragma unroll
-            for (int kk = 0; kk < KPF; ++kk) {
-                const int key = (kb0 + kk) * 32 + j;
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sacc[0][kk][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[0][s]) : "n"(2 * DS - 1 - 2 * s));
+                sacc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][s], qf[0][s], sacc[0][0], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);       // keep each product between its wait and the next
+                asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[1][s]) : "n"(2 * DS - 2 - 2 * s));
+                sacc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][s], qf[0][s], sacc[0][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                bf16x8 kf[DS];
+                const int key = kb * 32 + j;
                 const char *krow = Kt + key * ROWB;
                 const int ksw = Swz<D>::k(key);
 #pragma unroll
-                for (int s = 0; s < DS; ++s) kf[kk][s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
-            }
-            if (KPF == 2) __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the products
-#pragma unroll
-            for (int kk = 0; kk < KPF; ++kk) {
-                const int kb = kb0 + kk;
+                for (int s = 0; s < DS; ++s) kf[s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
 #pragma unroll
                 for (int qi = 0; qi < QB; ++qi)
 #pragma unroll
@@ -230,7 +255,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
                 for (int s = 0; s < DS; ++s)
 #pragma unroll
                     for (int qi = 0; qi < QB; ++qi)
-                        sacc[qi][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][s], qf[qi][s], sacc[qi][kb], 0, 0, 0);
+                        sacc[qi][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[qi][s], sacc[qi][kb], 0, 0, 0);
             }
         }
 
@@ -292,7 +317,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnArgs a)
     };
 
     // ---- O^T += V^T P^T for the tile whose weights are in pb
-    auto accumulate = [&](const char *Vt) {
+    auto accumulate = [&](const char *Vt) __attribute__((always_inline)) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll

@@ -218,12 +218,15 @@ tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
     return TLIN_OK;
 }
 
+// Ring depth per kernel shape (measured): a compute unit keeps little more than one tile of loads
+// in flight, so a deep ring only makes waves wait at the issue of loads that cannot start yet.  Two
+// stages also let two of the smaller workgroups share a compute unit.
 template <int D, bool CAUSAL>
 tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, 4>(a, grid, st);
-    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, 4>(a, grid, st);
-    return launch_bf16_shape<D, 2, 1, CAUSAL, 4>(a, grid, st);
+    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, CAUSAL ? 4 : 2>(a, grid, st);
+    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, CAUSAL ? 4 : 2>(a, grid, st);
+    return launch_bf16_shape<D, 2, 1, CAUSAL, CAUSAL ? 4 : 3>(a, grid, st);
 }
 
 // Key tiles the resident variant keeps in LDS (128 KB of keys and values).
