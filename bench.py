@@ -218,9 +218,11 @@ def main():
 
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (two runs of this script with --calibrate-copy; raw readings, commands and the scale factors of the
-# two counters are in profiles/attn_bf16_history_cfg4_pmc.md).  None = not measured for that workload.
+# two counters are in profiles/attn_bf16_history_cfg4_pmc.md and profiles/attn_bf16_history_decode_w1.md).
+# None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4_bf16_N131072_W512": 2_101_398 * 1024 + 33_280 * 1024,   # 2.004 GiB fetched + 32.5 MiB written
+    "cfg4_bf16_N131072_W512": int(1_050_690.8 * 2.0 * 1024) + 33_280 * 1024,   # 2.004 GiB fetched + 32.5 MiB written
+    "decode_bf16_N131072_W1": int(1_048_709.5 * 2.0 * 1024) + 260 * 1024,      # 2.0002 GiB fetched + 260 KiB written
 }
 
 
