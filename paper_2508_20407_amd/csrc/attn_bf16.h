@@ -76,9 +76,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // workgroup then walks over query blocks qb, qb + q_groups, ... without any further barrier, so
 // its waves drift apart and one wave's matrix work overlaps another's softmax arithmetic.  Used
 // where the query side is the long one.
+extern __shared__ __attribute__((aligned(1024))) char tlin_smem[];   // the tile ring: 2 * NSTAGE * TILE_B bytes
+
+// The work of one workgroup; `bid` of `nblocks` is its index among the blocks of this problem set.
 template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
-void attn_bf16_kernel(const AttnArgs a)
+__device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int nblocks)
 {
     static_assert(!(RESIDENT && CAUSAL), "the resident variant is for unmasked attention");
     constexpr int BN = 64;                 // keys per tile
@@ -95,15 +97,14 @@ void attn_bf16_kernel(const AttnArgs a)
     static_assert(PD >= 1, "ring too shallow");
     static_assert(PD * 2 * NDMA < 64, "too many loads in flight for vmcnt");
 
-    extern __shared__ __attribute__((aligned(1024))) char smem[];   // 2 * NSTAGE * TILE_B bytes
-    char *const Ks = smem;
-    char *const Vs = smem + NSTAGE * TILE_B;
+    char *const Ks = tlin_smem;
+    char *const Vs = tlin_smem + NSTAGE * TILE_B;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
 
-    const int L = xcd_remap(blockIdx.x, gridDim.x);
+    const int L = xcd_remap(bid, nblocks);
     const int qstep = RESIDENT ? a.q_groups : a.nqb;   // workgroups along the query axis of one head
     const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, qstep);
     if (pr.skip) return;                               // uniform over the workgroup
@@ -451,6 +452,22 @@ void attn_bf16_kernel(const AttnArgs a)
         }
     }
   } while (RESIDENT && qb < a.nqb);
+}
+
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
+void attn_bf16_kernel(const AttnArgs a)
+{
+    attn_bf16_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>(a, blockIdx.x, gridDim.x);
+}
+
+// History partition blocks and window causal blocks of one call in a single launch.
+template <int D, int NW, int NSTAGE>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
+void attn_bf16_pair_kernel(const PairArgs f)
+{
+    if ((int)blockIdx.x < f.n_hist_blocks) attn_bf16_body<D, NW, 1, false, NSTAGE>(f.hist, blockIdx.x, f.n_hist_blocks);
+    else attn_bf16_body<D, NW, 1, true, NSTAGE>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
 }
 
 }  // namespace tlin

@@ -67,6 +67,14 @@ struct MergeArgs {
     int32_t seq_rows;           // sliding schedule: output rows per head
 };
 
+// Two problem sets in one launch: the history partition blocks first (the long ones), then the
+// window causal blocks.  Kernel boundaries are expensive on this chip (the eight L2 caches are
+// written back and invalidated at each), and the short window blocks fill the tail of the long ones.
+struct PairArgs {
+    AttnArgs hist, win;
+    int32_t n_hist_blocks, n_win_blocks;
+};
+
 // Workgroups are dispatched round-robin over the 8 XCDs, each with a private L2.  Map the
 // hardware block id to a logical id such that consecutive logical ids run on the same XCD at
 // about the same time: neighbours that read the same K/V tiles then share that L2.

@@ -346,6 +346,53 @@ MergeArgs merge_args(const tlin_params *p, const Workspace &w, int nparts, int n
     return m;
 }
 
+template <int D, int NW, int NSTAGE>
+tlin_status launch_pair_shape(const PairArgs &f, hipStream_t st)
+{
+    constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
+    auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE>;
+    if (lds_bytes > 64 * 1024) {
+        static std::once_flag once;
+        static hipError_t err = hipSuccess;
+        std::call_once(once, [&] {
+            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        });
+        if (err != hipSuccess) return TLIN_ERR_HIP;
+    }
+    hipLaunchKernelGGL(kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
+    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+}
+
+// History partials and window partial of the same rows.  bf16: one launch for both problem sets.
+tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const AttnArgs &aw, hipStream_t hs)
+{
+    const int qblk = query_block(p->in_dtype, p->W);
+    const int nqb = (p->W + qblk - 1) / qblk;
+    const int64_t per_set = (int64_t)p->B * p->H * nqb * (ah.nchunks ? ah.nchunks : 1);
+    const int64_t nh = per_set * ah.nsplit, nw = per_set;
+    if (p->in_dtype == TLIN_BF16 && nh + nw <= 0x7fffffff) {
+        PairArgs f = {};
+        f.hist = ah;
+        f.win = aw;
+        f.hist.nqb = f.win.nqb = nqb;
+        f.n_hist_blocks = (int)nh;
+        f.n_win_blocks = (int)nw;
+        const Shape s = bf16_shape(p->W);
+        LaunchTimer timer(KC_HISTORY, hs);
+        if (p->D == 128) {
+            if (s.nw == 8) return launch_pair_shape<128, 8, 2>(f, hs);
+            if (s.nw == 4) return launch_pair_shape<128, 4, 2>(f, hs);
+            return launch_pair_shape<128, 2, 3>(f, hs);
+        }
+        if (s.nw == 8) return launch_pair_shape<64, 8, 2>(f, hs);
+        if (s.nw == 4) return launch_pair_shape<64, 4, 2>(f, hs);
+        return launch_pair_shape<64, 2, 3>(f, hs);
+    }
+    tlin_status st;
+    if ((st = launch_attn(p, false, ah, hs))) return st;
+    return launch_attn(p, true, aw, hs);
+}
+
 tlin_status check_ws(const void *ws, size_t have, size_t need)
 {
     if (need == 0) return TLIN_OK;
@@ -435,11 +482,9 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
     ah.nsplit = pl.nsplit;
     ah.tiles_per_split = pl.tiles_per_split;
     set_partial(ah, w, nparts, 0);
-    if ((st = launch_attn(p, false, ah, hs))) return st;
-
     AttnArgs aw = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
     set_partial(aw, w, nparts, pl.nsplit);
-    if ((st = launch_attn(p, true, aw, hs))) return st;
+    if ((st = launch_partials(p, ah, aw, hs))) return st;
 
     return launch_merge(p, merge_args(p, w, nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr), hs);
 }
@@ -481,15 +526,16 @@ tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const voi
         a.seq_rows = p->N;
         return a;
     };
-    if (pl.nchunks > 1) {
-        AttnArgs ah = args(K_hist, V_hist, p->kh_stride, p->vh_stride);
-        ah.nsplit = pl.nsplit;
-        set_partial(ah, w, pl.nparts, 0);
-        if ((st = launch_attn(p, false, ah, hs))) return st;
-    }
+    AttnArgs ah = args(K_hist, V_hist, p->kh_stride, p->vh_stride);
+    ah.nsplit = pl.nsplit;
+    set_partial(ah, w, pl.nparts, 0);
     AttnArgs aw = args(K_win, V_win, p->kw_stride, p->vw_stride);
     set_partial(aw, w, pl.nparts, pl.nsplit);
-    if ((st = launch_attn(p, true, aw, hs))) return st;
+    if (pl.nchunks > 1) {
+        if ((st = launch_partials(p, ah, aw, hs))) return st;
+    } else if ((st = launch_attn(p, true, aw, hs))) {
+        return st;
+    }
 
     MergeArgs m = merge_args(p, w, pl.nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr);
     m.o_sb = o.b; m.o_sh = o.h; m.o_sr = o.r;
