@@ -40,9 +40,13 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a)
         float M = -INFINITY;
         // joint slots: the history partials, then (JOINT) the window partial
         auto slot_of = [&](int s) { return s < nhist ? slot0 + s : wslot; };
+        // the loops are unrolled so that the loads of several partials are in flight together:
+        // with many partitions this kernel is bound by load latency, not by bytes
+#pragma unroll 8
         for (int s = 0; s < njoint; ++s) M = fmaxf(M, a.Mpart[slot_of(s) * a.W + row]);
         float den = 0.f;
         f32x4 num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
         for (int s = 0; s < njoint; ++s) {
             const int64_t idx = slot_of(s) * a.W + row;
             const float w = exp2f(a.Mpart[idx] - M);

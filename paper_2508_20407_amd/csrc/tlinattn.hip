@@ -37,8 +37,9 @@ int query_block(int in_dtype, int W) { return in_dtype == TLIN_F32 ? 32 : bf16_s
 int resident_wgs(int in_dtype, int W)
 {
     if (in_dtype == TLIN_F32) return kNumCU * 2;
-    const Shape s = bf16_shape(W);
-    return kNumCU * (s.bm() >= 256 ? 1 : 2);
+    // eight- and two-wave workgroups fill a compute unit alone (registers, LDS ring); two of the
+    // four-wave ones share it
+    return kNumCU * (bf16_shape(W).nw == 4 ? 2 : 1);
 }
 
 // ---- measurement aid: per-kernel timing with HIP events on the launch stream
@@ -135,11 +136,14 @@ Plan plan_history(const tlin_params *p)
     if (p->num_splits > 0) {
         want = p->num_splits;
     } else {
-        // Enough workgroups to occupy every compute unit, but at least 4 tiles per partition.
+        // Enough workgroups to occupy every compute unit, but at least 8 tiles per partition: the
+        // merge reads every partial, and with short partitions it would cost more than they save.
         const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W) - 1) / query_block(p->in_dtype, p->W));
         const int64_t target = resident_wgs(p->in_dtype, p->W);
         want = (int)((target + base - 1) / base);
-        const int cap = ntiles / 4 > 1 ? ntiles / 4 : 1;
+        // (fp32 tiles are vector-ALU work and take several times longer: 4 are enough there)
+        const int min_tiles = p->in_dtype == TLIN_F32 ? 4 : 8;
+        const int cap = ntiles / min_tiles > 1 ? ntiles / min_tiles : 1;
         if (want > cap) want = cap;
     }
     if (want < 1) want = 1;
