@@ -225,11 +225,11 @@ def main():
 
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (two runs of this script with --calibrate-copy; raw readings, commands and the scale factors of the
-# two counters are in profiles/attn_bf16_history_cfg4_pmc.md and profiles/attn_bf16_history_decode_w1.md).
+# two counters are in profiles/attn_bf16_pair_cfg4_pmc.md and profiles/attn_bf16_history_decode_w1.md).
 # None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4_bf16_N131072_W512": int(1_050_690.8 * 2.0 * 1024) + 33_280 * 1024,   # 2.004 GiB fetched + 32.5 MiB written
-    "decode_bf16_N131072_W1": int(1_048_709.5 * 2.0 * 1024) + 260 * 1024,      # 2.0002 GiB fetched + 260 KiB written
+    "cfg4_bf16_N131072_W512": int(1_056_902.3 * 2.0 * 1024) + 41_600 * 1024,   # 2.016 GiB fetched + 40.6 MiB written
+    "decode_bf16_N131072_W1": int(1_048_703.1 * 2.0 * 1024) + 130 * 1024,      # 2.0002 GiB fetched + 130 KiB written
 }
 
 

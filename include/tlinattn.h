@@ -119,7 +119,7 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
  * whose history is every earlier chunk, so row c*W + i attends rows [0, c*W) of K_hist/V_hist
  * without a mask and rows [c*W, c*W + i] of K_win/V_win causally, joined per p->combine.
  * Chunk 0 has an empty history.  Equivalent to one tlin_layer_attn call per chunk; done as
- * three launches for all chunks together, the longest histories scheduled first.
+ * a few launches for all chunks together, the longest histories scheduled first.
  *   Q, K_hist, V_hist, K_win, V_win: [B,H,N,D] in in_dtype; O [B,H,N,D] in out_dtype.
  *   K_hist/V_hist may be the same buffers as K_win/V_win (one projection for both roles).
  *   p->num_splits: partitions per chunk history; 0 = choose automatically.
