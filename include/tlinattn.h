@@ -22,7 +22,11 @@
  *   - All tensor pointers and the workspace are DEVICE pointers owned by the caller.  The
  *     library never allocates, frees or keeps them.  Inputs are read-only; O must not alias
  *     an input.  Layout is [B, H, rows, D] with D contiguous; batch/head/row strides are given
- *     in elements (0 in every slot of a stride triple = dense).
+ *     in elements (0 in every slot of a stride triple = dense).  Rows are read and written in
+ *     16-byte pieces: every stride must be a multiple of 16 bytes, and a row must own D elements
+ *     rounded up to whole pieces (so bf16 with D = 36 needs a row stride of at least 40, and a
+ *     dense layout needs D itself to be whole pieces).  What the inputs hold between D and the end
+ *     of the last piece is ignored; in O those elements are left untouched.
  *   - Calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and return without synchronising.  Calls using the same workspace must be ordered on
  *     one stream.
@@ -68,7 +72,8 @@ typedef struct {
     int32_t N;           /* history rows; >= 1 for tlin_history_attn, >= 0 for tlin_layer_attn,
                             ignored by tlin_window_causal_attn; sequence rows (>= 1) for
                             tlin_slide_layer_attn, whose chunk length is W */
-    int32_t D;           /* head dimension: 64 or 128 */
+    int32_t D;           /* head dimension: a multiple of 4 in [8, 128]; 64 and 128 are the native
+                            sizes, others run in the next of the two (see the layout rules) */
     int32_t in_dtype;    /* tlin_dtype of Q, K, V */
     int32_t out_dtype;   /* tlin_dtype of O */
     float scale;         /* logit multiplier, finite and > 0; 1/sqrt(D) gives the paper's formula */

@@ -78,8 +78,13 @@ def _stream(t):
 
 
 def _out(q, out_dtype):
+    """Output tensor [B,H,rows,D]; its rows are padded to whole 16-byte pieces when D is not."""
     torch = _torch()
-    return torch.empty(q.shape, dtype=q.dtype if out_dtype is None else out_dtype, device=q.device)
+    dt = q.dtype if out_dtype is None else out_dtype
+    per16 = 16 // torch.empty((), dtype=dt).element_size()
+    B, H, R, D = q.shape
+    row = (D + per16 - 1) // per16 * per16
+    return torch.empty((B, H, R, row), dtype=dt, device=q.device)[..., :D]
 
 
 def tlin_history_attn(q_win, k_hist, v_hist, *, scale=None, out_dtype=None, num_splits=0, return_lse=False,

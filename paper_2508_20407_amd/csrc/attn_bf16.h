@@ -79,7 +79,8 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 extern __shared__ __attribute__((aligned(1024))) char tlin_smem[];   // the tile ring: 2 * NSTAGE * TILE_B bytes
 
 // The work of one workgroup; `bid` of `nblocks` is its index among the blocks of this problem set.
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
+// PAD: the tensors' head dimension a.D is smaller than the kernel's D.
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false, bool PAD = false>
 __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int nblocks)
 {
     static_assert(!(RESIDENT && CAUSAL), "the resident variant is for unmasked attention");
@@ -128,16 +129,38 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
     const char *Kg = (const char *)((const __bf16 *)a.K + (int64_t)b * a.k_sb + (int64_t)hd * a.k_sh) + pr.krow_off * k_rb;
     const char *Vg = (const char *)((const __bf16 *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh) + pr.krow_off * v_rb;
 
+    // Tensors with a head dimension a.D below the kernel's D: whole 16-byte chunks of a row exist
+    // up to dchunks; Q is taken as zero from column a.D on, and K is cleared from there in the one
+    // fragment that straddles a.D (what lies between a.D and the end of that chunk is the
+    // caller's padding and may hold anything).
+    const int dchunks = PAD ? (a.D + 7) >> 3 : D / 8;
+    const int straddle = (PAD && (a.D & 7)) ? (a.D >> 4) : -1;   // contraction step whose fragment straddles a.D
+    // clears the elements from column a.D on in the fragment of that step (computed where needed:
+    // the mask is not kept in registers, the step is rare)
+    auto clip = [&](bf16x8 f) __attribute__((always_inline)) {
+        const int keep = a.D - (16 * straddle + 8 * h);     // elements this lane keeps (may be <= 0 or >= 8)
+        u32x4 u = __builtin_bit_cast(u32x4, f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u[e] &= keep >= 2 * e + 2 ? ~0u : keep == 2 * e + 1 ? 0x0000ffffu : 0u;
+        return __builtin_bit_cast(bf16x8, u);
+    };
+
     int qrow0 = qb * BM + wave * (QB * 32);
     bf16x8 qf[QB][DS];
     // Q^T fragments (B operand): lane holds query j, contraction elements 16*s + 8*h .. +7.
+    // fragment of contraction step s of the query row at qp (columns from a.D on count as zeros)
+    auto q_fragment = [&](const __bf16 *qp, int s) __attribute__((always_inline)) {
+        if (PAD && 16 * s + 8 * h >= a.D) return bf16x8{};
+        const bf16x8 f = *(const bf16x8 *)(qp + 16 * s);
+        return (PAD && s == straddle) ? clip(f) : f;
+    };
     auto load_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int qi = 0; qi < QB; ++qi) {
             const int r = min(qrow0 + qi * 32 + j, Wq - 1);
             const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
 #pragma unroll
-            for (int s = 0; s < DS; ++s) qf[qi][s] = *(const bf16x8 *)(qp + 16 * s);
+            for (int s = 0; s < DS; ++s) qf[qi][s] = q_fragment(qp, s);
         }
         // Consume the Q registers here, so that the wait for these loads sits before the tile loop
         // and not inside it, where it would also wait for the tile loads in flight.
@@ -155,8 +178,14 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
 #pragma unroll
     for (int i = 0; i < NDMA; ++i) {
         drow[i] = (wave * NDMA + i) * RPI + lane / CPR;
-        koff[i] = drow[i] * k_rb + (((lane % CPR) ^ Swz<D>::k(drow[i])) << 4);
-        voff[i] = drow[i] * v_rb + (((lane % CPR) ^ Swz<D>::v(drow[i])) << 4);
+        // rows shorter than the kernel's D (a.D < D): chunks past the end of a row are not in
+        // memory; chunk 0 (complete, as a.D >= 8) is fetched in their place (they only meet zero columns of Q, and the
+        // output columns they produce are not stored)
+        int kc = (lane % CPR) ^ Swz<D>::k(drow[i]), vc = (lane % CPR) ^ Swz<D>::v(drow[i]);
+        if (PAD && kc >= dchunks) kc = 0;
+        if (PAD && vc >= dchunks) vc = 0;
+        koff[i] = drow[i] * k_rb + (kc << 4);
+        voff[i] = drow[i] * v_rb + (vc << 4);
     }
     auto issue = [&](int t, int stage) __attribute__((always_inline)) {
         const int key0 = t * BN;
@@ -233,9 +262,11 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[0][s]) : "n"(2 * DS - 1 - 2 * s));
+                if (PAD && s == straddle) kf[0][s] = clip(kf[0][s]);
                 sacc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][s], qf[0][s], sacc[0][0], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);       // keep each product between its wait and the next
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[1][s]) : "n"(2 * DS - 2 - 2 * s));
+                if (PAD && s == straddle) kf[1][s] = clip(kf[1][s]);
                 sacc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][s], qf[0][s], sacc[0][1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -247,7 +278,10 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
                 const char *krow = Kt + key * ROWB;
                 const int ksw = Swz<D>::k(key);
 #pragma unroll
-                for (int s = 0; s < DS; ++s) kf[s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
+                for (int s = 0; s < DS; ++s) {
+                    kf[s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
+                    if (PAD && s == straddle) kf[s] = clip(kf[s]);
+                }
 #pragma unroll
                 for (int qi = 0; qi < QB; ++qi)
 #pragma unroll
@@ -374,7 +408,7 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
                 const int r = min(nrow0 + qi * 32 + j, Wq - 1);
                 const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
 #pragma unroll
-                for (int s = 0; s < DS; ++s) qn[qi][s] = *(const bf16x8 *)(qp + 16 * s);
+                for (int s = 0; s < DS; ++s) qn[qi][s] = q_fragment(qp, s);
             }
         }
         for (int t = 0; t < t1; ++t) {
@@ -409,6 +443,7 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int d = 32 * db + 8 * g + 4 * h;
+                    if (PAD && d >= a.D) continue;       // column beyond the tensors' head dimension
                     f32x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = oacc[qi][db][4 * g + e] * inv;
@@ -454,20 +489,20 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
   } while (RESIDENT && qb < a.nqb);
 }
 
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false, bool PAD = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
 void attn_bf16_kernel(const AttnArgs a)
 {
-    attn_bf16_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>(a, blockIdx.x, gridDim.x);
+    attn_bf16_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>(a, blockIdx.x, gridDim.x);
 }
 
 // History partition blocks and window causal blocks of one call in a single launch.
-template <int D, int NW, int NSTAGE>
+template <int D, int NW, int NSTAGE, bool PAD = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
 void attn_bf16_pair_kernel(const PairArgs f)
 {
-    if ((int)blockIdx.x < f.n_hist_blocks) attn_bf16_body<D, NW, 1, false, NSTAGE>(f.hist, blockIdx.x, f.n_hist_blocks);
-    else attn_bf16_body<D, NW, 1, true, NSTAGE>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
+    if ((int)blockIdx.x < f.n_hist_blocks) attn_bf16_body<D, NW, 1, false, NSTAGE, false, PAD>(f.hist, blockIdx.x, f.n_hist_blocks);
+    else attn_bf16_body<D, NW, 1, true, NSTAGE, false, PAD>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
 }
 
 }  // namespace tlin

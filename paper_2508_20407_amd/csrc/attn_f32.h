@@ -53,7 +53,9 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
     for (int i = tid; i < BM * (D / 4); i += NT) {
         const int r = i / (D / 4), c4 = i % (D / 4);
         const int gr = min(qrow0 + r, Wq - 1);
-        *(f32x4 *)(Qs + r * LDQ + 4 * c4) = *(const f32x4 *)(Qg + (int64_t)gr * a.q_sr + 4 * c4);
+        // columns beyond the tensors' head dimension a.D count as zeros
+        *(f32x4 *)(Qs + r * LDQ + 4 * c4) =
+            4 * c4 < a.D ? *(const f32x4 *)(Qg + (int64_t)gr * a.q_sr + 4 * c4) : f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     // score / value-product ownership: rows 2*ty, 2*ty+1; score columns tx + 16*c
@@ -74,8 +76,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
         for (int i = tid; i < BN * (D / 4); i += NT) {
             const int r = i / (D / 4), c4 = i % (D / 4);
             const int gr = min(key0 + r, NK - 1);
-            *(f32x4 *)(Ks + r * LDQ + 4 * c4) = *(const f32x4 *)(Kg + (int64_t)gr * a.k_sr + 4 * c4);
-            *(f32x4 *)(Vs + r * D + 4 * c4) = *(const f32x4 *)(Vg + (int64_t)gr * a.v_sr + 4 * c4);
+            const bool in = 4 * c4 < a.D;
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            *(f32x4 *)(Ks + r * LDQ + 4 * c4) = in ? *(const f32x4 *)(Kg + (int64_t)gr * a.k_sr + 4 * c4) : zero;
+            *(f32x4 *)(Vs + r * D + 4 * c4) = in ? *(const f32x4 *)(Vg + (int64_t)gr * a.v_sr + 4 * c4) : zero;
         }
         __syncthreads();
 
@@ -181,6 +185,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a)
 #pragma unroll
             for (int c = 0; c < CPT; ++c) {
                 const int d = 4 * tx + 64 * c;
+                if (d >= a.D) continue;
                 const f32x4 o = oacc[r][c] * inv;
                 if (a.out_bf16) {
                     bf16x4 ob;

@@ -25,6 +25,7 @@ struct AttnArgs {
     int64_t k_sb, k_sh, k_sr;
     int64_t v_sb, v_sh, v_sr;
     int32_t H;                  // heads per batch (to split the flat batch*head index)
+    int32_t D;                  // head dimension of the tensors; the kernel's D when equal, else smaller
     int32_t W;                  // query rows
     int32_t NK;                 // key rows
     int32_t nqb;                // query blocks per head
@@ -62,6 +63,7 @@ struct MergeArgs {
     int64_t o_sb, o_sh, o_sr;
     float *lse;                 // nullable
     int32_t out_bf16;
+    int32_t D;                  // columns of O to store (the kernel's D, or fewer)
     int32_t total_rows;         // BH * W (sliding schedule: BH * seq_rows)
     int32_t nchunks;            // sliding schedule: chunks of W rows per head (0 otherwise); chunk 0 has no history
     int32_t seq_rows;           // sliding schedule: output rows per head

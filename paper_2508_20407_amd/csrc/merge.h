@@ -62,7 +62,9 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a)
     }
 
     const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)orow * a.o_sr + c4;
-    if (a.out_bf16) {
+    if (c4 >= a.D) {
+        // column beyond the tensors' head dimension: nothing to store
+    } else if (a.out_bf16) {
         bf16x4 ob;
 #pragma unroll
         for (int e = 0; e < 4; ++e) ob[e] = (__bf16)o[e];

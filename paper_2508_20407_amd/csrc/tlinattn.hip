@@ -30,6 +30,10 @@ Shape bf16_shape(int W)
     return {2, 1};
 }
 
+// Head dimensions other than 64 and 128 run in the next of the two kernel sizes: the kernels
+// treat the missing columns of Q as zeros and do not store the extra output columns.
+int dpad(int D) { return D <= 64 ? 64 : 128; }
+
 int key_tile(int in_dtype, int D) { return (in_dtype == TLIN_F32 && D == 128) ? 32 : 64; }
 int query_block(int in_dtype, int W) { return in_dtype == TLIN_F32 ? 32 : bf16_shape(W).bm(); }
 
@@ -92,14 +96,29 @@ Strides resolve(const int64_t s[3], int H, int rows, int D)
 
 tlin_status check_strides(const int64_t s[3], int D, int elem_bytes)
 {
-    if (dense(s)) return TLIN_OK;
     const int per16 = 16 / elem_bytes;
-    if (s[2] < D || s[0] < 0 || s[1] < 0) return TLIN_ERR_INVALID_ARG;
+    // rows are read in 16-byte pieces: a row holds D elements rounded up to whole pieces
+    const int row_elems = (D + per16 - 1) / per16 * per16;
+    if (dense(s)) return TLIN_OK;   // whether a dense layout is possible is checked per call, for the tensors it uses
+    if (s[2] < row_elems || s[0] < 0 || s[1] < 0) return TLIN_ERR_INVALID_ARG;
     if (s[0] % per16 || s[1] % per16 || s[2] % per16) return TLIN_ERR_INVALID_ARG;
     return TLIN_OK;
 }
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// A tensor given without strides is dense, which needs rows of whole 16-byte pieces.
+enum Tensor { T_Q = 1, T_KH = 2, T_VH = 4, T_KW = 8, T_VW = 16, T_O = 32 };
+tlin_status check_dense_rows(const tlin_params *p, int used)
+{
+    const int in16 = 16 / (p->in_dtype == TLIN_F32 ? 4 : 2), out16 = 16 / (p->out_dtype == TLIN_F32 ? 4 : 2);
+    const struct { int bit; const int64_t *s; int per16; } t[] = {
+        {T_Q, p->q_stride, in16}, {T_KH, p->kh_stride, in16}, {T_VH, p->vh_stride, in16},
+        {T_KW, p->kw_stride, in16}, {T_VW, p->vw_stride, in16}, {T_O, p->o_stride, out16}};
+    for (const auto &x : t)
+        if ((used & x.bit) && dense(x.s) && p->D % x.per16) return TLIN_ERR_INVALID_ARG;
+    return TLIN_OK;
+}
 
 tlin_status check_common(const tlin_params *p, bool need_history, bool allow_empty_history)
 {
@@ -109,7 +128,7 @@ tlin_status check_common(const tlin_params *p, bool need_history, bool allow_emp
     if (need_history && (p->N < (allow_empty_history ? 0 : 1))) return TLIN_ERR_INVALID_ARG;
     if (p->in_dtype != TLIN_F32 && p->in_dtype != TLIN_BF16) return TLIN_ERR_INVALID_ARG;
     if (p->out_dtype != TLIN_F32 && p->out_dtype != TLIN_BF16) return TLIN_ERR_INVALID_ARG;
-    if (p->D != 64 && p->D != 128) return TLIN_ERR_UNSUPPORTED;
+    if (p->D < 8 || p->D > 128 || p->D % 4) return TLIN_ERR_UNSUPPORTED;
     if (!(p->scale > 0.f) || !isfinite(p->scale)) return TLIN_ERR_INVALID_ARG;
     if (p->num_splits < 0) return TLIN_ERR_INVALID_ARG;
     const int eb = p->in_dtype == TLIN_F32 ? 4 : 2;
@@ -130,7 +149,7 @@ struct Plan { int nsplit, tiles_per_split; };
 Plan plan_history(const tlin_params *p)
 {
     if (p->N < 1) return {0, 0};
-    const int bn = key_tile(p->in_dtype, p->D);
+    const int bn = key_tile(p->in_dtype, dpad(p->D));
     const int ntiles = (p->N + bn - 1) / bn;
     int want;
     if (p->num_splits > 0) {
@@ -160,7 +179,7 @@ struct SlidePlan { int nchunks, nsplit, nparts; };
 SlidePlan plan_slide(const tlin_params *p)
 {
     const int nchunks = (p->N + p->W - 1) / p->W;
-    const int bn = key_tile(p->in_dtype, p->D);
+    const int bn = key_tile(p->in_dtype, dpad(p->D));
     const int qblk = query_block(p->in_dtype, p->W);
     const int nqb = (p->W + qblk - 1) / qblk;
     int want;
@@ -185,13 +204,13 @@ SlidePlan plan_slide(const tlin_params *p)
 size_t slide_ws_bytes(const tlin_params *p, const SlidePlan &pl)
 {
     const size_t rows = (size_t)p->B * p->H * pl.nchunks * pl.nparts * p->W;
-    return rows * p->D * sizeof(float) + 2 * rows * sizeof(float);
+    return rows * dpad(p->D) * sizeof(float) + 2 * rows * sizeof(float);
 }
 
 size_t ws_bytes_for(const tlin_params *p, int nparts)
 {
     const size_t rows = (size_t)p->B * p->H * nparts * p->W;
-    return rows * p->D * sizeof(float) + 2 * rows * sizeof(float);
+    return rows * dpad(p->D) * sizeof(float) + 2 * rows * sizeof(float);
 }
 
 struct Workspace { float *O, *M, *L; };
@@ -200,15 +219,15 @@ Workspace carve(void *ws, const tlin_params *p, int nparts)
 {
     const size_t rows = (size_t)p->B * p->H * nparts * p->W;
     float *base = (float *)ws;
-    return {base, base + rows * p->D, base + rows * p->D + rows};
+    return {base, base + rows * dpad(p->D), base + rows * dpad(p->D) + rows};
 }
 
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
-tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT, bool PAD>
+tlin_status launch_bf16_shape_pad(const AttnArgs &a, int grid, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>;
+    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>;
     if (lds_bytes > 64 * 1024) {
         // more than 64 KB of dynamic LDS has to be allowed once per kernel
         static std::once_flag once;
@@ -220,6 +239,15 @@ tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
     }
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
     return TLIN_OK;
+}
+
+// The variant with a.D below the kernel's D is a kernel of its own, so that the exact sizes carry
+// none of its code.
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false>
+tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
+{
+    if (a.D != D) return launch_bf16_shape_pad<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, true>(a, grid, st);
+    return launch_bf16_shape_pad<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, false>(a, grid, st);
 }
 
 // Ring depth per kernel shape (measured): a compute unit keeps little more than one tile of loads
@@ -244,7 +272,7 @@ bool use_resident(const tlin_params *p, bool causal, const AttnArgs &a)
     if (bf16_shape(p->W).nw != 8) return false;
     const int ntiles = (a.NK + 63) / 64;
     const int64_t blocks = (int64_t)p->B * p->H * a.nqb;
-    return ntiles <= resident_tiles(p->D) && blocks >= 4 * (int64_t)kNumCU;
+    return ntiles <= resident_tiles(dpad(p->D)) && blocks >= 4 * (int64_t)kNumCU;
 }
 
 // Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
@@ -261,7 +289,7 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
         const int64_t grid64 = bh * g;
         if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
         LaunchTimer timer(KC_HISTORY, st);
-        const tlin_status rc = p->D == 128 ? launch_bf16_shape<128, 8, 1, false, 4, true>(a, (int)grid64, st)
+        const tlin_status rc = dpad(p->D) == 128 ? launch_bf16_shape<128, 8, 1, false, 4, true>(a, (int)grid64, st)
                                            : launch_bf16_shape<64, 8, 1, false, 8, true>(a, (int)grid64, st);
         if (rc != TLIN_OK) return rc;
         return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
@@ -273,11 +301,11 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
     if (p->in_dtype == TLIN_BF16) {
         const Shape s = bf16_shape(p->W);
         tlin_status rc;
-        if (p->D == 128) rc = causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
+        if (dpad(p->D) == 128) rc = causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
         else rc = causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
         if (rc != TLIN_OK) return rc;
     } else {
-        if (p->D == 128) {
+        if (dpad(p->D) == 128) {
             if (causal) hipLaunchKernelGGL((attn_f32_kernel<128, true>), dim3(grid), dim3(256), 0, st, a);
             else hipLaunchKernelGGL((attn_f32_kernel<128, false>), dim3(grid), dim3(256), 0, st, a);
         } else {
@@ -293,13 +321,14 @@ tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
     m.H = p->H;
     m.W = p->W;
     m.out_bf16 = p->out_dtype == TLIN_BF16;
+    m.D = p->D;
     const int64_t total = (int64_t)p->B * p->H * (m.nchunks ? m.seq_rows : p->W);
     if (total > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     m.total_rows = (int)total;
-    const int rpb = 256 / (p->D / 4);
+    const int rpb = 256 / (dpad(p->D) / 4);
     const int grid = (int)((total + rpb - 1) / rpb);
     LaunchTimer timer(KC_MERGE, st);
-    if (p->D == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, st, m);
+    if (dpad(p->D) == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, st, m);
     else hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, st, m);
     return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
 }
@@ -316,6 +345,7 @@ AttnArgs base_args(const tlin_params *p, const void *Q, const void *K, const voi
     a.k_sb = k.b; a.k_sh = k.h; a.k_sr = k.r;
     a.v_sb = v.b; a.v_sh = v.h; a.v_sr = v.r;
     a.H = p->H; a.W = p->W; a.NK = nk;
+    a.D = p->D;
     a.nsplit = 1; a.tiles_per_split = 0x3fffffff;
     a.scale = p->scale;
     a.c = p->scale * 1.4426950408889634f;
@@ -350,11 +380,11 @@ MergeArgs merge_args(const tlin_params *p, const Workspace &w, int nparts, int n
     return m;
 }
 
-template <int D, int NW, int NSTAGE>
-tlin_status launch_pair_shape(const PairArgs &f, hipStream_t st)
+template <int D, int NW, int NSTAGE, bool PAD>
+tlin_status launch_pair_shape_pad(const PairArgs &f, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
-    auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE>;
+    auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE, PAD>;
     if (lds_bytes > 64 * 1024) {
         static std::once_flag once;
         static hipError_t err = hipSuccess;
@@ -365,6 +395,13 @@ tlin_status launch_pair_shape(const PairArgs &f, hipStream_t st)
     }
     hipLaunchKernelGGL(kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
     return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+}
+
+template <int D, int NW, int NSTAGE>
+tlin_status launch_pair_shape(const PairArgs &f, hipStream_t st)
+{
+    if (f.hist.D != D) return launch_pair_shape_pad<D, NW, NSTAGE, true>(f, st);
+    return launch_pair_shape_pad<D, NW, NSTAGE, false>(f, st);
 }
 
 // History partials and window partial of the same rows.  bf16: one launch for both problem sets.
@@ -383,7 +420,7 @@ tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const Attn
         f.n_win_blocks = (int)nw;
         const Shape s = bf16_shape(p->W);
         LaunchTimer timer(KC_HISTORY, hs);
-        if (p->D == 128) {
+        if (dpad(p->D) == 128) {
             if (s.nw == 8) return launch_pair_shape<128, 8, 2>(f, hs);
             if (s.nw == 4) return launch_pair_shape<128, 4, 2>(f, hs);
             return launch_pair_shape<128, 2, 3>(f, hs);
@@ -426,6 +463,7 @@ tlin_status tlin_history_attn(const tlin_params *p, const void *Q_win, const voi
 {
     tlin_status st = check_common(p, true, false);
     if (st) return st;
+    if ((st = check_dense_rows(p, T_Q | T_KH | T_VH | T_O))) return st;
     if (!Q_win || !K_hist || !V_hist || !O) return TLIN_ERR_INVALID_ARG;
     if (!aligned(Q_win, 16) || !aligned(K_hist, 16) || !aligned(V_hist, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
     if (lse && !aligned(lse, 4)) return TLIN_ERR_INVALID_ARG;
@@ -452,6 +490,7 @@ tlin_status tlin_window_causal_attn(const tlin_params *p, const void *Q_win, con
     (void)ws_bytes;
     tlin_status st = check_common(p, false, false);
     if (st) return st;
+    if ((st = check_dense_rows(p, T_Q | T_KW | T_VW | T_O))) return st;
     if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
     if (!aligned(Q_win, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
     if (lse && !aligned(lse, 4)) return TLIN_ERR_INVALID_ARG;
@@ -465,6 +504,7 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
 {
     tlin_status st = check_common(p, true, true);
     if (st) return st;
+    if ((st = check_dense_rows(p, T_Q | T_KW | T_VW | T_O | (p->N > 0 ? T_KH | T_VH : 0)))) return st;
     if (p->combine != TLIN_COMBINE_SUM && p->combine != TLIN_COMBINE_JOINT) return TLIN_ERR_INVALID_ARG;
     if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
     if (p->N > 0 && (!K_hist || !V_hist)) return TLIN_ERR_INVALID_ARG;
@@ -506,6 +546,7 @@ tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const voi
 {
     tlin_status st = check_common(p, true, false);
     if (st) return st;
+    if ((st = check_dense_rows(p, T_Q | T_KH | T_VH | T_KW | T_VW | T_O))) return st;
     if (p->combine != TLIN_COMBINE_SUM && p->combine != TLIN_COMBINE_JOINT) return TLIN_ERR_INVALID_ARG;
     if (!Q || !K_hist || !V_hist || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
     if (!aligned(Q, 16) || !aligned(K_hist, 16) || !aligned(V_hist, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) ||
@@ -518,7 +559,7 @@ tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const voi
     // partial slots: (b*H + h, chunk, part), W rows each
     const size_t rows = (size_t)p->B * p->H * pl.nchunks * pl.nparts * p->W;
     float *base = (float *)ws;
-    const Workspace w = {base, base + rows * p->D, base + rows * p->D + rows};
+    const Workspace w = {base, base + rows * dpad(p->D), base + rows * dpad(p->D) + rows};
 
     // every tensor has p->N rows per head
     const Strides q = resolve(p->q_stride, p->H, p->N, p->D);

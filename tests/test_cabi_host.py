@@ -57,7 +57,7 @@ def test_workspace_and_split_planning_is_pure_host_arithmetic():
     assert b.num_splits(P(num_splits=5)) == 4      # 16 tiles: 4 per partition, none empty
     assert b.num_splits(P(num_splits=10 ** 6)) == 1024 // 64   # one 64-key tile per partition at most
     assert b.num_splits(P(N=1)) == 1
-    assert b.workspace_bytes(P(W=0)) == 0 and b.num_splits(P(D=96)) == 0
+    assert b.workspace_bytes(P(W=0)) == 0 and b.num_splits(P(D=30)) == 0
 
 
 A = 1 << 20   # a fake, suitably aligned device address: validation must fail before it is used
@@ -65,7 +65,8 @@ A = 1 << 20   # a fake, suitably aligned device address: validation must fail be
 
 @pytest.mark.parametrize("kw,status", [
     (dict(B=0), b.TLIN_ERR_INVALID_ARG), (dict(H=-1), b.TLIN_ERR_INVALID_ARG), (dict(W=0), b.TLIN_ERR_INVALID_ARG),
-    (dict(N=0), b.TLIN_ERR_INVALID_ARG), (dict(D=96), b.TLIN_ERR_UNSUPPORTED), (dict(D=256), b.TLIN_ERR_UNSUPPORTED),
+    (dict(N=0), b.TLIN_ERR_INVALID_ARG), (dict(D=30), b.TLIN_ERR_UNSUPPORTED), (dict(D=256), b.TLIN_ERR_UNSUPPORTED), (dict(D=0), b.TLIN_ERR_UNSUPPORTED), (dict(D=4), b.TLIN_ERR_UNSUPPORTED),
+    (dict(D=36), b.TLIN_ERR_INVALID_ARG),                                      # dense bf16 rows of 72 bytes
     (dict(in_dtype=7), b.TLIN_ERR_INVALID_ARG), (dict(out_dtype=-1), b.TLIN_ERR_INVALID_ARG),
     (dict(scale=0.0), b.TLIN_ERR_INVALID_ARG), (dict(scale=float("nan")), b.TLIN_ERR_INVALID_ARG),
     (dict(scale=float("inf")), b.TLIN_ERR_INVALID_ARG), (dict(num_splits=-2), b.TLIN_ERR_INVALID_ARG),
@@ -74,6 +75,21 @@ A = 1 << 20   # a fake, suitably aligned device address: validation must fail be
 ])
 def test_history_rejects_bad_params(kw, status):
     assert b.history_attn_raw(P(**kw), A, A, A, A, None, A, 1 << 30, None) == status
+
+
+def test_other_head_dimensions_run_in_the_next_native_size():
+    # rows padded to whole 16-byte pieces are accepted; the workspace is sized for the kernel's 64 / 128 columns
+    st40 = lambda rows: (2 * rows * 40, rows * 40, 40)
+    p36 = P(D=36, q_stride=st40(64), kh_stride=st40(1024), vh_stride=st40(1024), kw_stride=st40(64), vw_stride=st40(64),
+            o_stride=st40(64))
+    assert b.num_splits(p36) == b.num_splits(P()) and b.workspace_bytes(p36) == b.workspace_bytes(P())
+    p96 = P(D=96)
+    assert b.workspace_bytes(p96) == b.workspace_bytes(P(D=128))
+    # fp32 rows of 36 floats are whole pieces already
+    assert b.num_splits(P(D=36, in_dtype=b.TLIN_F32, out_dtype=b.TLIN_F32)) >= 1
+    # a row stride that cannot hold the last piece
+    bad = P(D=36, q_stride=(2 * 64 * 36, 64 * 36, 36))
+    assert b.history_attn_raw(bad, A, A, A, A, None, A, 1 << 30, None) == b.TLIN_ERR_INVALID_ARG
 
 
 def test_null_and_misaligned_pointers_and_workspace():
@@ -107,7 +123,7 @@ def test_slide_planning_and_argument_checks():
     assert need % (8 * per_slot) == 0 and need // (8 * per_slot) >= 2
     forced = P(B=1, H=1, W=128, N=1000, D=64, num_splits=3)
     assert b.slide_workspace_bytes(forced) == 8 * 4 * per_slot
-    assert b.slide_workspace_bytes(P(N=0)) == 0 and b.slide_workspace_bytes(P(D=96)) == 0
+    assert b.slide_workspace_bytes(P(N=0)) == 0 and b.slide_workspace_bytes(P(D=130)) == 0
     big = 1 << 40
     assert b.slide_layer_attn_raw(P(N=0), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
     assert b.slide_layer_attn_raw(P(combine=2), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG

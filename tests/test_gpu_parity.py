@@ -217,6 +217,68 @@ def test_slide_full_size_sampled_rows():
     run_slide(w, 512, rows=rows)
 
 
+# ---------------------------------------------------------------- head dimensions between the native sizes
+def padded(a: np.ndarray, dtype: int) -> torch.Tensor:
+    """Device tensor whose rows are padded to whole 16-byte pieces; the padding holds NaNs (it
+    must be ignored), the view handed to the library has the logical head dimension."""
+    t = to_device_any(a, dtype)
+    per16 = 16 // t.element_size()
+    D = t.shape[-1]
+    row = (D + per16 - 1) // per16 * per16
+    buf = torch.full(t.shape[:-1] + (row,), float("nan"), dtype=t.dtype, device=t.device)
+    buf[..., :D] = t
+    return buf[..., :D]
+
+
+def to_device_any(a, dtype):
+    from helpers import to_device
+    return to_device(a, dtype)
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("D", [36, 8, 12, 60, 96, 100])
+@pytest.mark.parametrize("W,N", [(1, 700), (70, 333), (256, 2100), (300, 64)])
+def test_head_dimensions_between_the_native_sizes(dtype, D, W, N):
+    """The paper's own model has head dimension 36 (432 / 12, Section 6.2)."""
+    w = ti.Workload(f"hd_{dtype}_{D}_{W}_{N}", 1, 3, D, N, W, dtype, 1.0, 3636 + D + W + N)
+    host = ti.make(w)
+    dev = {k: padded(v, w.dtype) for k, v in host.items()}
+    o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, return_lse=True)
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    assert o.shape[-1] == D
+    assert_close(o, ro, w.dtype, f"{w.name} history")
+    np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+    o = tl.tlin_window_causal_attn(dev["Q"], dev["Kw"], dev["Vw"], scale=w.scale)
+    ro, _ = oracle.window_causal(host["Q"], host["Kw"], host["Vw"], w.dtype, w.scale)
+    assert_close(o, ro, w.dtype, f"{w.name} window")
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], combine=mode, scale=w.scale)
+        ro = oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, omode)
+        assert_close(o, ro, w.dtype, f"{w.name} layer mode {mode}")
+
+
+def test_paper_model_shape_head_dimension_36_full_size_sampled_rows():
+    """12 heads of dimension 36, windows of 256 rows (Sections 5.1 and 6.2), 131072 history rows."""
+    w = ti.Workload("paper_hd36", 1, 12, 36, 131072, 256, ti.BF16, 1.0, 36036)
+    host = ti.make(w)
+    dev = {k: padded(v, w.dtype) for k, v in host.items()}
+    rows = sample_rows(w.W, 6, seed=36)
+    idx = torch.from_numpy(rows).long().cuda()
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], combine=mode, scale=w.scale)
+        ro = oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, omode, rows)
+        assert_close(o[:, :, idx], ro, w.dtype, f"{w.name} mode {mode}")
+    # cache-hit step and restoration shape of the same model
+    q1 = dev["Q"][:, :, -1:, :]
+    o = tl.tlin_history_attn(q1, dev["Kh"], dev["Vh"], scale=w.scale)
+    ro, _ = oracle.history(host["Q"][:, :, -1:, :], host["Kh"], host["Vh"], w.dtype, w.scale)
+    assert_close(o, ro, w.dtype, "paper_hd36 cache-hit step")
+    o = tl.tlin_history_attn(dev["Kh"][:, :, :40000], dev["Kw"], dev["Vw"], scale=w.scale)     # many queries x 256 keys
+    rr = sample_rows(40000, 24, seed=37)
+    ro, _ = oracle.history(host["Kh"][:, :, :40000], host["Kw"], host["Vw"], w.dtype, w.scale, rr)
+    assert_close(o[:, :, torch.from_numpy(rr).long().cuda()], ro, w.dtype, "paper_hd36 restoration")
+
+
 # ---------------------------------------------------------------- shapes, tails, degenerate cases
 @pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
 @pytest.mark.parametrize("D", [64, 128])
