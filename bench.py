@@ -40,13 +40,15 @@ def parse():
     ap.add_argument("--combine", choices=("sum", "joint"), default="sum")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--sweep", action="store_true", help="latency-vs-N sweep instead of the single workload")
-    ap.add_argument("--workload", choices=("config", "decode", "restore", "slide"), default="config",
+    ap.add_argument("--workload", choices=("config", "decode", "restore", "slide", "paper"), default="config",
                     help="config: --config's layer call (default). decode: the cache-hit step of Section 4.2, "
                          "--W newest rows (default 1) query --N history rows (default 131072) through "
                          "tlin_history_attn. restore: the context path's last layer, --N history rows (default "
                          "131072) query --W compressed rows (default 256) through tlin_history_attn. slide: the "
                          "sliding schedule of Section 5.1 over a sequence of --N rows (default 131072) in chunks of "
-                         "--W rows (default 512) through tlin_slide_layer_attn")
+                         "--W rows (default 512) through tlin_slide_layer_attn. paper: the layer call at the paper's "
+                         "own model shape, 12 heads of dimension 36, --W window rows (default 256; 1 = cache-hit "
+                         "step through tlin_history_attn) over --N history rows (default 131072)")
     ap.add_argument("--N", type=int, default=None)
     ap.add_argument("--W", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -58,10 +60,18 @@ def parse():
 
 
 def upload(host, dtype, ti, torch, np):
+    """Device copies; rows are padded to whole 16-byte pieces when the head dimension is not."""
     dev = {}
     for k, a in host.items():
-        dev[k] = (torch.from_numpy(a).cuda() if dtype == ti.F32
-                  else torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16))
+        t = (torch.from_numpy(a).cuda() if dtype == ti.F32
+             else torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16))
+        per16 = 16 // t.element_size()
+        D = t.shape[-1]
+        if D % per16:
+            buf = torch.zeros(t.shape[:-1] + ((D + per16 - 1) // per16 * per16,), dtype=t.dtype, device=t.device)
+            buf[..., :D] = t
+            t = buf[..., :D]
+        dev[k] = t
     return dev
 
 
@@ -126,11 +136,16 @@ def main():
     if args.workload == "slide":
         return slide(args, ti, tl, binding, torch, np, combine)
 
-    layer = args.workload == "config"
-    if layer:
+    layer = args.workload == "config" or (args.workload == "paper" and (args.W or 256) > 1)
+    if args.workload == "config":
         w = ti.config(args.config - 1)
         metric = "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak"
         what = "tlin_layer_attn = history partitions + window causal (one launch for bf16) + merge"
+    elif args.workload == "paper":
+        w = ti.paper_model_point(args.N or 131072, args.W or 256)
+        metric = "attention of the paper's own model shape (12 heads x 36), bf16"
+        what = ("tlin_layer_attn = history partitions + window causal + merge" if layer else
+                "tlin_history_attn = history partitions + merge (cache-hit step)")
     elif args.workload == "decode":
         w = ti.decode_point(args.N or 131072, args.W or 1)
         metric = "cache-hit step: newest rows x N-row history, bf16; % HBM peak"

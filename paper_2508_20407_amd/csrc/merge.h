@@ -13,46 +13,75 @@
 
 namespace tlin {
 
-template <int D>
+// SL threads ("slot lanes") share one (row, 4 columns) item: lane sl takes the partials
+// sl, sl + SL, ... and the SL running results are joined through LDS.  With many partitions the
+// kernel is bound by the latency of its dependent loads, not by bytes, so the partials of a row are
+// spread over threads instead of being walked by one.
+template <int D, int SL>
 __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a)
 {
-    constexpr int TPR = D / 4;                 // threads per row, 4 columns each
-    constexpr int RPB = 256 / TPR;             // rows per block
+    constexpr int TPR = D / 4;                 // column groups per row, 4 columns each
+    constexpr int RPB = 256 / (TPR * SL);      // rows per block
+    static_assert(RPB >= 1, "a row must fit in a block");
+    __shared__ float red[SL > 1 ? 256 * 6 : 1];
+
     const int tid = threadIdx.x;
-    const int64_t grow = (int64_t)blockIdx.x * RPB + tid / TPR;   // flat row index over (b,h,row)
-    if (grow >= a.total_rows) return;
-    const int c4 = (tid % TPR) * 4;
+    const int cg = tid % TPR, sl = (tid / TPR) % SL, rb = tid / (TPR * SL);
+    const int64_t grow = (int64_t)blockIdx.x * RPB + rb;          // flat row index over (b,h,row)
+    const bool live = grow < a.total_rows;
+    const int c4 = cg * 4;
     // Sliding schedule: the row belongs to chunk orow / W of its head, the partials of a chunk sit
     // in its own group of slots, and chunk 0 has no history partials.
     const int rows_per_head = a.nchunks ? a.seq_rows : a.W;
-    const int bh = (int)(grow / rows_per_head), orow = (int)(grow % rows_per_head);
+    const int bh = live ? (int)(grow / rows_per_head) : 0, orow = live ? (int)(grow % rows_per_head) : 0;
     const int chunk = a.nchunks ? orow / a.W : 0;
     const int row = orow - chunk * a.W;
     const int b = bh / a.H, hd = bh % a.H;
     const int64_t slot0 = ((int64_t)bh * (a.nchunks ? a.nchunks : 1) + chunk) * a.nparts;
     const int nhist = (a.nchunks && chunk == 0) ? 0 : a.nhist;
     const int64_t wslot = slot0 + a.nhist;             // the window partial's slot
+    const int njoint = live ? nhist + ((a.has_window && a.joint) ? 1 : 0) : 0;
+    // joint slots: the history partials, then (JOINT) the window partial
+    auto slot_of = [&](int s) { return s < nhist ? slot0 + s : wslot; };
 
-    const int njoint = nhist + ((a.has_window && a.joint) ? 1 : 0);
+    // this lane's share of the joint partials, relative to its own maximum
+    float M = -INFINITY, den = 0.f;
+    f32x4 num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int s = sl; s < njoint; s += SL) M = fmaxf(M, a.Mpart[slot_of(s) * a.W + row]);
+#pragma unroll 4
+    for (int s = sl; s < njoint; s += SL) {
+        const int64_t idx = slot_of(s) * a.W + row;
+        const float ms = a.Mpart[idx];
+        const float w = ms == -INFINITY ? 0.f : exp2f(ms - M);     // an empty partition holds -inf and zeros
+        den += w * a.Lpart[idx];
+        num += w * *(const f32x4 *)(a.Opart + idx * D + c4);
+    }
+    if (SL > 1) {
+        float *mine = red + tid * 6;
+        mine[0] = M; mine[1] = den; mine[2] = num[0]; mine[3] = num[1]; mine[4] = num[2]; mine[5] = num[3];
+        __syncthreads();
+        if (sl != 0) return;
+        float Mt = M;
+#pragma unroll
+        for (int k = 1; k < SL; ++k) Mt = fmaxf(Mt, red[(tid + k * TPR) * 6]);
+        const float w0 = M == -INFINITY ? 0.f : exp2f(M - Mt);     // a lane without partials holds -inf
+        den *= w0;
+        num *= w0;
+#pragma unroll
+        for (int k = 1; k < SL; ++k) {
+            const float *o = red + (tid + k * TPR) * 6;
+            const float w = o[0] == -INFINITY ? 0.f : exp2f(o[0] - Mt);
+            den += w * o[1];
+            num += w * f32x4{o[2], o[3], o[4], o[5]};
+        }
+        M = Mt;
+    }
+    if (!live) return;
+
     f32x4 o = {0.f, 0.f, 0.f, 0.f};
     float lse2 = -INFINITY;
     if (njoint > 0) {
-        float M = -INFINITY;
-        // joint slots: the history partials, then (JOINT) the window partial
-        auto slot_of = [&](int s) { return s < nhist ? slot0 + s : wslot; };
-        // the loops are unrolled so that the loads of several partials are in flight together:
-        // with many partitions this kernel is bound by load latency, not by bytes
-#pragma unroll 8
-        for (int s = 0; s < njoint; ++s) M = fmaxf(M, a.Mpart[slot_of(s) * a.W + row]);
-        float den = 0.f;
-        f32x4 num = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-        for (int s = 0; s < njoint; ++s) {
-            const int64_t idx = slot_of(s) * a.W + row;
-            const float w = exp2f(a.Mpart[idx] - M);
-            den += w * a.Lpart[idx];
-            num += w * *(const f32x4 *)(a.Opart + idx * D + c4);
-        }
         o = num * (1.0f / den);
         lse2 = M + log2f(den);
     }

@@ -38,11 +38,13 @@ int key_tile(int in_dtype, int D) { return (in_dtype == TLIN_F32 && D == 128) ? 
 int query_block(int in_dtype, int W) { return in_dtype == TLIN_F32 ? 32 : bf16_shape(W).bm(); }
 
 // Workgroups the chip holds at once for a given kernel shape (LDS- and register-limited).
-int resident_wgs(int in_dtype, int W)
+int resident_wgs(int in_dtype, int W, int D)
 {
     if (in_dtype == TLIN_F32) return kNumCU * 2;
-    // eight- and two-wave workgroups fill a compute unit alone (registers, LDS ring); two of the
-    // four-wave ones share it
+    // head dimension 64: tiles and register sets are half as large, three workgroups share a
+    // compute unit (measured best for few heads); 128: eight- and two-wave workgroups fill a compute
+    // unit alone (registers, LDS ring), two of the four-wave ones share it
+    if (dpad(D) == 64) return kNumCU * 3;
     return kNumCU * (bf16_shape(W).nw == 4 ? 2 : 1);
 }
 
@@ -158,7 +160,7 @@ Plan plan_history(const tlin_params *p)
         // Enough workgroups to occupy every compute unit, but at least 8 tiles per partition: the
         // merge reads every partial, and with short partitions it would cost more than they save.
         const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W) - 1) / query_block(p->in_dtype, p->W));
-        const int64_t target = resident_wgs(p->in_dtype, p->W);
+        const int64_t target = resident_wgs(p->in_dtype, p->W, p->D);
         want = (int)((target + base - 1) / base);
         // (fp32 tiles are vector-ALU work and take several times longer: 4 are enough there)
         const int min_tiles = p->in_dtype == TLIN_F32 ? 4 : 8;
@@ -189,7 +191,7 @@ SlidePlan plan_slide(const tlin_params *p)
         // With many chunks the work items (head, chunk, query block) already outnumber the compute
         // units several times and the long ones start first; split only short sequences.
         const int64_t items = (int64_t)p->B * p->H * nqb * (nchunks > 1 ? nchunks - 1 : 1);
-        const int64_t target = 2 * (int64_t)resident_wgs(p->in_dtype, p->W);
+        const int64_t target = 2 * (int64_t)resident_wgs(p->in_dtype, p->W, p->D);
         want = (int)((target + items - 1) / items);
     }
     // at least 4 tiles per partition in the longest history
@@ -325,11 +327,21 @@ tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
     const int64_t total = (int64_t)p->B * p->H * (m.nchunks ? m.seq_rows : p->W);
     if (total > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     m.total_rows = (int)total;
-    const int rpb = 256 / (dpad(p->D) / 4);
+    // threads per (row, 4 columns) item: more when a row has many partials to walk
+    const int joint = m.nhist + (m.has_window && m.joint ? 1 : 0);
+    const int sl = joint > 16 ? 8 : joint > 6 ? 4 : 1;
+    const int rpb = 256 / (dpad(p->D) / 4 * sl);
     const int grid = (int)((total + rpb - 1) / rpb);
     LaunchTimer timer(KC_MERGE, st);
-    if (dpad(p->D) == 128) hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, st, m);
-    else hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, st, m);
+    if (dpad(p->D) == 128) {
+        if (sl == 8) hipLaunchKernelGGL((merge_kernel<128, 8>), dim3(grid), dim3(256), 0, st, m);
+        else if (sl == 4) hipLaunchKernelGGL((merge_kernel<128, 4>), dim3(grid), dim3(256), 0, st, m);
+        else hipLaunchKernelGGL((merge_kernel<128, 1>), dim3(grid), dim3(256), 0, st, m);
+    } else {
+        if (sl == 8) hipLaunchKernelGGL((merge_kernel<64, 8>), dim3(grid), dim3(256), 0, st, m);
+        else if (sl == 4) hipLaunchKernelGGL((merge_kernel<64, 4>), dim3(grid), dim3(256), 0, st, m);
+        else hipLaunchKernelGGL((merge_kernel<64, 1>), dim3(grid), dim3(256), 0, st, m);
+    }
     return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
 }
 

@@ -120,6 +120,13 @@ def restore_point(n_queries: int, w_oh: int = 256) -> Workload:
                     _BASE_SEED + 7 + 7919 * w_oh + 104729 * n_queries)
 
 
+def paper_model_point(N: int, W: int = 256) -> Workload:
+    """The attention shape of the paper's own model (Section 6.2: width 432 in 12 heads, so head
+    dimension 36; windows of 256 rows, Section 5.1) over an N-row history."""
+    return Workload(f"paper_bf16_H12_D36_N{N}_W{W}", 1, 12, 36, N, W, BF16, 1.0,
+                    _BASE_SEED + 8 + 7919 * N + 104729 * W)
+
+
 def degenerate_causal() -> Workload:
     """Empty history, window of 4096 rows: the layer reduces to standard causal attention."""
     return sweep_point(0, 4096)
