@@ -130,9 +130,10 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
     const char *Vg = (const char *)((const __bf16 *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh) + pr.krow_off * v_rb;
 
     // Tensors with a head dimension a.D below the kernel's D: whole 16-byte chunks of a row exist
-    // up to dchunks; Q is taken as zero from column a.D on, and K is cleared from there in the one
-    // fragment that straddles a.D (what lies between a.D and the end of that chunk is the
-    // caller's padding and may hold anything).
+    // up to dchunks; Q is taken as zero from column a.D on, and in the one chunk of a K row that
+    // straddles a.D the part from a.D on (the caller's padding, which may hold anything) is
+    // cleared in LDS by the wave that loaded the row, between its wait for the load and the
+    // tile's barrier.
     const int dchunks = PAD ? (a.D + 7) >> 3 : D / 8;
     const int straddle = (PAD && (a.D & 7)) ? (a.D >> 4) : -1;   // contraction step whose fragment straddles a.D
     // clears the elements from column a.D on in the fragment of that step (computed where needed:
@@ -209,6 +210,18 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
         }
     };
 
+    // PAD, a.D not a multiple of 8: clears elements a.D .. of the straddling chunk (8 bytes: a.D is
+    // a multiple of 4) in the K rows of a stage that this wave loaded; lane i takes the i-th of them
+    auto scrub = [&](int stage) __attribute__((always_inline)) {
+        if (!PAD || !(a.D & 7)) return;
+        if (lane < NDMA * RPI) {
+            const int r = (wave * NDMA + lane / RPI) * RPI + lane % RPI;      // tile row
+            const int pos = (a.D >> 3) ^ Swz<D>::k(r);                        // where its straddling chunk sits
+            *(u32x2 *)(Ks + stage * TILE_B + r * ROWB + (pos << 4) + 8) = u32x2{0u, 0u};
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // written before the barrier is passed
+    };
+
     f32x16 oacc[QB][DB];
     float m[QB], l[QB];
     auto reset = [&]() __attribute__((always_inline)) {
@@ -262,11 +275,9 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[0][s]) : "n"(2 * DS - 1 - 2 * s));
-                if (PAD && s == straddle) kf[0][s] = clip(kf[0][s]);
                 sacc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][s], qf[0][s], sacc[0][0], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);       // keep each product between its wait and the next
                 asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(kf[1][s]) : "n"(2 * DS - 2 - 2 * s));
-                if (PAD && s == straddle) kf[1][s] = clip(kf[1][s]);
                 sacc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][s], qf[0][s], sacc[0][1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -278,10 +289,7 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
                 const char *krow = Kt + key * ROWB;
                 const int ksw = Swz<D>::k(key);
 #pragma unroll
-                for (int s = 0; s < DS; ++s) {
-                    kf[s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
-                    if (PAD && s == straddle) kf[s] = clip(kf[s]);
-                }
+                for (int s = 0; s < DS; ++s) kf[s] = *(const bf16x8 *)(krow + (((2 * s + h) ^ ksw) << 4));
 #pragma unroll
                 for (int qi = 0; qi < QB; ++qi)
 #pragma unroll
@@ -392,6 +400,9 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
             if (s < t1) issue(s, s);
         load_q();
         wait_vmcnt<0>();
+#pragma unroll
+        for (int s = 0; s < NSTAGE; ++s)
+            if (s < t1) scrub(s);
         __builtin_amdgcn_s_barrier();
     } else {
 #pragma unroll
@@ -420,6 +431,7 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
             const int n = t - t0;
             if (t + PD - 1 < t1) wait_vmcnt<(PD - 1) * PER_TILE>();   // PD-1 younger tiles may still fly
             else wait_vmcnt<0>();
+            scrub(n % NSTAGE);
             __builtin_amdgcn_s_barrier();
             if (t + PD < t1) issue(t + PD, (n + PD) % NSTAGE);
             if (active(t)) {
