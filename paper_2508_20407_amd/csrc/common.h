@@ -104,7 +104,8 @@ template <int BM, int BN, bool CAUSAL>
 __device__ __forceinline__ Problem decode_problem(const AttnArgs &a, int L, int qstep)
 {
     Problem p;
-    p.qb = L % qstep;
+    // causal blocks grow with the block index: the long ones are started first
+    p.qb = CAUSAL ? qstep - 1 - L % qstep : L % qstep;
     int rest = L / qstep;
     p.split = rest % a.nsplit;
     rest /= a.nsplit;
