@@ -30,6 +30,9 @@
 //     direct loads write LDS linearly, so the swizzle is applied on the source side: the lane
 //     that lands on chunk position c of row r fetches chunk c ^ swz(r) of that row.
 #pragma once
+#ifndef TLIN_BUFLOAD
+#define TLIN_BUFLOAD 1
+#endif
 #include "common.h"
 
 namespace tlin {
@@ -58,6 +61,27 @@ __device__ __forceinline__ void direct_load_1k(const char *gsrc, unsigned lds_ba
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :
                  : "s"(lds_base), "v"(gsrc)
+                 : "memory", "m0");
+}
+
+// The same through a buffer descriptor: the tile's base address sits in scalar registers and a
+// lane contributes a 32-bit byte offset, which the address unit handles faster than 64-bit
+// per-lane addresses.  Offsets at or beyond `bytes` read as zeros (raw buffer, stride 0).
+__device__ __forceinline__ u32x4 tile_descriptor(const char *base, unsigned bytes)
+{
+    const uint64_t b = (uint64_t)base;
+    u32x4 d;
+    d[0] = __builtin_amdgcn_readfirstlane((unsigned)b);
+    d[1] = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32) & 0xffffu);   // stride 0, no swizzle
+    d[2] = __builtin_amdgcn_readfirstlane(bytes);
+    d[3] = 0x00020000u;                                                       // raw 32-bit data format
+    return d;
+}
+__device__ __forceinline__ void direct_load_1k(u32x4 desc, unsigned byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(byte_off), "s"(desc)
                  : "memory", "m0");
 }
 
@@ -175,38 +199,32 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
     // Direct load i of this wave covers tile rows (wave*NDMA + i)*RPI .. +RPI-1; this lane lands
     // on row drow[i], chunk position lane % CPR, and so fetches chunk (lane % CPR) ^ swz(row).
     int drow[NDMA];
-    int64_t koff[NDMA], voff[NDMA];
+    unsigned koff[NDMA], voff[NDMA];       // byte offsets inside a tile (the host bounds the row strides)
 #pragma unroll
     for (int i = 0; i < NDMA; ++i) {
         drow[i] = (wave * NDMA + i) * RPI + lane / CPR;
         // rows shorter than the kernel's D (a.D < D): chunks past the end of a row are not in
-        // memory; chunk 0 (complete, as a.D >= 8) is fetched in their place (they only meet zero columns of Q, and the
-        // output columns they produce are not stored)
+        // memory; chunk 0 (complete, as a.D >= 8) is fetched in their place (they only meet zero
+        // columns of Q, and the output columns they produce are not stored)
         int kc = (lane % CPR) ^ Swz<D>::k(drow[i]), vc = (lane % CPR) ^ Swz<D>::v(drow[i]);
         if (PAD && kc >= dchunks) kc = 0;
         if (PAD && vc >= dchunks) vc = 0;
-        koff[i] = drow[i] * k_rb + (kc << 4);
-        voff[i] = drow[i] * v_rb + (vc << 4);
+        koff[i] = (unsigned)(drow[i] * k_rb) + (kc << 4);
+        voff[i] = (unsigned)(drow[i] * v_rb) + (vc << 4);
     }
     auto issue = [&](int t, int stage) __attribute__((always_inline)) {
         const int key0 = t * BN;
         const unsigned kdst = __builtin_amdgcn_readfirstlane(lds_offset(Ks) + stage * TILE_B + wave * (NDMA * 1024));
         const unsigned vdst = kdst + NSTAGE * TILE_B;
-        if (key0 + BN <= NK) {
-            const char *kt = Kg + key0 * k_rb, *vt = Vg + key0 * v_rb;
+        // rows past the end of the tensor (ragged last tile) lie beyond the descriptor's size and
+        // arrive as zeros; their scores are masked
+        const int rows = min(BN, NK - key0);
+        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
+        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
 #pragma unroll
-            for (int i = 0; i < NDMA; ++i) {
-                direct_load_1k(kt + koff[i], kdst + i * 1024);
-                direct_load_1k(vt + voff[i], vdst + i * 1024);
-            }
-        } else {
-            // ragged last tile: rows past the end repeat the last row (their scores are masked)
-#pragma unroll
-            for (int i = 0; i < NDMA; ++i) {
-                const int64_t back = max(key0 + drow[i] - (NK - 1), 0);
-                direct_load_1k(Kg + (key0 - back) * k_rb + koff[i], kdst + i * 1024);
-                direct_load_1k(Vg + (key0 - back) * v_rb + voff[i], vdst + i * 1024);
-            }
+        for (int i = 0; i < NDMA; ++i) {
+            direct_load_1k(kd, koff[i], kdst + i * 1024);
+            direct_load_1k(vd, voff[i], vdst + i * 1024);
         }
     };
 
@@ -251,7 +269,7 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
         // Register budget decides how the K fragments come from LDS.  AHEAD: all fragments of the
         // tile are requested back to back before the first product.  Otherwise one 32-key block
         // at a time, under the compiler's own waits.
-        constexpr bool AHEAD = QB == 1 && !(CAUSAL && D == 128);
+        constexpr bool AHEAD = QB == 1;
         if constexpr (AHEAD) {
             // Requests go out in the order the products consume them (contraction step outer,
             // 32-key block inner), and every product waits only until its own operand has

@@ -103,6 +103,8 @@ tlin_status check_strides(const int64_t s[3], int D, int elem_bytes)
     const int row_elems = (D + per16 - 1) / per16 * per16;
     if (dense(s)) return TLIN_OK;   // whether a dense layout is possible is checked per call, for the tensors it uses
     if (s[2] < row_elems || s[0] < 0 || s[1] < 0) return TLIN_ERR_INVALID_ARG;
+    // a tile of 64 rows is addressed with 32-bit byte offsets
+    if (s[2] * elem_bytes >= (int64_t)1 << 25) return TLIN_ERR_INVALID_ARG;
     if (s[0] % per16 || s[1] % per16 || s[2] % per16) return TLIN_ERR_INVALID_ARG;
     return TLIN_OK;
 }
