@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--N", type=int, default=None)
     ap.add_argument("--W", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemm-context", action="store_true",
+                    help="skip the library bf16 GEMM timed after the steps (context figure for matrix-core-bound workloads)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, so that a rocprofv3 --pmc run of this "
@@ -106,6 +108,28 @@ def rotating(Kh, Vh, torch):
         return kv_sets[turn[0]]
 
     return next_kv, n_kv
+
+
+def gemm_context(torch, n=8192, iters=50):
+    """Context only, never the target: the rate the vendor library's plain bf16 matrix product
+    (torch.matmul) sustains on this GPU right after the timed steps.  Under sustained matrix-core load
+    the chip clocks well below the 2.4 GHz that the published peak assumes, so this is the practical
+    ceiling for a dense contraction on the box the run landed on."""
+    try:
+        a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+        b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+        for _ in range(10):
+            a @ b
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(iters):
+            a @ b
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t) / iters
+        return {"library_bf16_gemm_TFLOPs": 2.0 * n ** 3 / dt / 1e12, "shape": f"{n}x{n}x{n}",
+                "kind": "torch.matmul, same GPU, same run"}
+    except Exception as e:                   # a context figure must never fail the bench
+        return {"library_bf16_gemm_TFLOPs": None, "error": repr(e)}
 
 
 def cpu_baseline(w, host, target_s, oracle, np, layer=True):
@@ -258,6 +282,10 @@ def main():
         "kernels_ms": {"history": hist_ms, "window_causal": win_ms, "merge": merge_ms},
         "roofline": roof,
     }
+    if roof["bound"] == "mfma" and not args.no_gemm_context:
+        out["context"] = gemm_context(torch)
+        if out["context"].get("library_bf16_gemm_TFLOPs"):
+            out["context"]["kernel_vs_library_gemm"] = hist_tflops / out["context"]["library_bf16_gemm_TFLOPs"]
     if not args.no_cpu_baseline:
         import oracle
         out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np, layer)
