@@ -297,8 +297,8 @@ def main():
 # two counters are in profiles/attn_bf16_pair_cfg4_pmc.md and profiles/attn_bf16_history_decode_w1.md).
 # None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4_bf16_N131072_W512": int(1_056_902.3 * 2.0 * 1024) + 41_600 * 1024,   # 2.016 GiB fetched + 40.6 MiB written
-    "decode_bf16_N131072_W1": int(1_048_703.1 * 2.0 * 1024) + 130 * 1024,      # 2.0002 GiB fetched + 130 KiB written
+    "cfg4_bf16_N131072_W512": int(1_056_884.3 * 2.0 * 1024) + 41_600 * 1024,   # 2.016 GiB fetched + 40.6 MiB written
+    "decode_bf16_N131072_W1": int(1_048_681.2 * 2.0 * 1024) + 130 * 1024,      # 2.0002 GiB fetched + 130 KiB written
 }
 
 
