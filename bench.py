@@ -228,6 +228,17 @@ def main():
 
     sec = time_steps(step, args.steps, args.warmup, torch)
 
+    # Spread of single steps: the same K steps again, each between its own pair of events on the
+    # launch stream (torch's current stream, which the binding passes to the library).
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    step_median, step_min = per_step[len(per_step) // 2], per_step[0]
+
     # Per-kernel durations: the same K steps again with event pairs around every launch.
     binding.profile_enable(True)
     for _ in range(args.steps):
@@ -271,7 +282,8 @@ def main():
     out = {
         "metric": metric,
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": sec * 1e3, "ms_per_step_median": step_median, "ms_per_step_min": step_min,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == ti.F32 else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "D": w.D, "N_history": w.N, "W_window": w.W,
                    "combine": args.combine, "num_splits": binding.num_splits(tl.params_for(Q, w.N, num_splits=args.num_splits)),

@@ -68,7 +68,7 @@ typedef enum { TLIN_COMBINE_SUM = 0, TLIN_COMBINE_JOINT = 1 } tlin_combine;
 
 typedef struct {
     int32_t B, H;        /* batch, heads: B*H independent problems, each >= 1 */
-    int32_t W;           /* window (query) rows, >= 1 */
+    int32_t W;           /* window (query) rows, >= 1; W and N are at most 2^30 */
     int32_t N;           /* history rows; >= 1 for tlin_history_attn, >= 0 for tlin_layer_attn,
                             ignored by tlin_window_causal_attn; sequence rows (>= 1) for
                             tlin_slide_layer_attn, whose chunk length is W */
@@ -79,8 +79,8 @@ typedef struct {
     float scale;         /* logit multiplier, finite and > 0; 1/sqrt(D) gives the paper's formula */
     int32_t num_splits;  /* partitions of the history axis; 0 = choose automatically */
     int32_t combine;     /* tlin_combine, used by tlin_layer_attn only */
-    /* element strides {batch, head, row}; all three 0 = dense.  Row strides must be >= D and
-     * keep every row 16-byte aligned. */
+    /* element strides {batch, head, row}; all three 0 = dense.  Row strides must be >= D, keep
+     * every row 16-byte aligned and stay below 32 MiB. */
     int64_t q_stride[3], kh_stride[3], vh_stride[3], kw_stride[3], vw_stride[3], o_stride[3];
 } tlin_params;
 

@@ -268,8 +268,9 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
         f32x16 sacc[QB][2];
         // Register budget decides how the K fragments come from LDS.  AHEAD: all fragments of the
         // tile are requested back to back before the first product.  Otherwise one 32-key block
-        // at a time, under the compiler's own waits.
-        constexpr bool AHEAD = QB == 1;
+        // at a time, under the compiler's own waits (the resident variant also holds the next
+        // block's queries and would spill; its waves are not in lock-step, so it gains nothing).
+        constexpr bool AHEAD = QB == 1 && !RESIDENT;
         if constexpr (AHEAD) {
             // Requests go out in the order the products consume them (contraction step outer,
             // 32-key block inner), and every product waits only until its own operand has

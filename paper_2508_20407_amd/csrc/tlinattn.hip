@@ -4,6 +4,7 @@
 
 #include <math.h>
 
+#include <atomic>
 #include <mutex>
 #include <utility>
 #include <vector>
@@ -17,6 +18,7 @@ using namespace tlin;
 namespace {
 
 constexpr int kVersion = 100;   // 0.1.0
+constexpr int kMaxRows = 1 << 30;
 
 struct Strides { int64_t b, h, r; };
 
@@ -53,7 +55,7 @@ enum KernelClass { KC_HISTORY = 0, KC_WINDOW = 1, KC_MERGE = 2, KC_COUNT = 3 };
 
 struct Timed { int cls; hipEvent_t start, stop; };
 struct Profiler {
-    bool on = false;
+    std::atomic<bool> on{false};
     std::vector<Timed> used;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
     std::mutex mu;
@@ -71,7 +73,7 @@ struct LaunchTimer {
         if (g_prof.pool.empty()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess) return;
-            if (hipEventCreate(&b) != hipSuccess) { hipEventDestroy(a); return; }
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
             g_prof.pool.push_back({a, b});
         }
         t = {cls, g_prof.pool.back().first, g_prof.pool.back().second};
@@ -82,9 +84,10 @@ struct LaunchTimer {
     ~LaunchTimer()
     {
         if (!active) return;
-        hipEventRecord(t.stop, st);
+        const bool ok = hipEventRecord(t.stop, st) == hipSuccess;
         std::lock_guard<std::mutex> lk(g_prof.mu);
-        g_prof.used.push_back(t);
+        if (ok) g_prof.used.push_back(t);
+        else g_prof.pool.push_back({t.start, t.stop});
     }
 };
 
@@ -128,6 +131,7 @@ tlin_status check_common(const tlin_params *p, bool need_history, bool allow_emp
 {
     if (!p) return TLIN_ERR_INVALID_ARG;
     if (p->B < 1 || p->H < 1 || p->W < 1) return TLIN_ERR_INVALID_ARG;
+    if (p->W > kMaxRows || p->N > kMaxRows) return TLIN_ERR_INVALID_ARG;   // tile counts and row indices are 32-bit
     if ((int64_t)p->B * p->H > (1 << 24)) return TLIN_ERR_INVALID_ARG;
     if (need_history && (p->N < (allow_empty_history ? 0 : 1))) return TLIN_ERR_INVALID_ARG;
     if (p->in_dtype != TLIN_F32 && p->in_dtype != TLIN_BF16) return TLIN_ERR_INVALID_ARG;
@@ -226,21 +230,29 @@ Workspace carve(void *ws, const tlin_params *p, int nparts)
     return {base, base + rows * dpad(p->D), base + rows * dpad(p->D) + rows};
 }
 
+// More than 64 KB of dynamic LDS has to be allowed once per kernel and device.  `done` is the
+// calling kernel's own record: one bit per device ordinal.
+tlin_status allow_lds(const void *kernel, int lds_bytes, std::atomic<uint64_t> &done)
+{
+    if (lds_bytes <= 64 * 1024) return TLIN_OK;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TLIN_ERR_HIP;
+    const uint64_t bit = (uint64_t)1 << dev;
+    if (done.load(std::memory_order_acquire) & bit) return TLIN_OK;
+    // two threads may both get here: setting the attribute twice is harmless
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) return TLIN_ERR_HIP;
+    done.fetch_or(bit, std::memory_order_release);
+    return TLIN_OK;
+}
+
 template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT, bool PAD>
 tlin_status launch_bf16_shape_pad(const AttnArgs &a, int grid, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
     auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>;
-    if (lds_bytes > 64 * 1024) {
-        // more than 64 KB of dynamic LDS has to be allowed once per kernel
-        static std::once_flag once;
-        static hipError_t err = hipSuccess;
-        std::call_once(once, [&] {
-            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        });
-        if (err != hipSuccess) return TLIN_ERR_HIP;
-    }
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
     return TLIN_OK;
 }
@@ -398,15 +410,10 @@ template <int D, int NW, int NSTAGE, bool PAD>
 tlin_status launch_pair_shape_pad(const PairArgs &f, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
+    static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
     auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE, PAD>;
-    if (lds_bytes > 64 * 1024) {
-        static std::once_flag once;
-        static hipError_t err = hipSuccess;
-        std::call_once(once, [&] {
-            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        });
-        if (err != hipSuccess) return TLIN_ERR_HIP;
-    }
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
     hipLaunchKernelGGL(kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
     return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
 }

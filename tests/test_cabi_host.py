@@ -70,6 +70,8 @@ A = 1 << 20   # a fake, suitably aligned device address: validation must fail be
     (dict(in_dtype=7), b.TLIN_ERR_INVALID_ARG), (dict(out_dtype=-1), b.TLIN_ERR_INVALID_ARG),
     (dict(scale=0.0), b.TLIN_ERR_INVALID_ARG), (dict(scale=float("nan")), b.TLIN_ERR_INVALID_ARG),
     (dict(scale=float("inf")), b.TLIN_ERR_INVALID_ARG), (dict(num_splits=-2), b.TLIN_ERR_INVALID_ARG),
+    (dict(N=(1 << 30) + 1), b.TLIN_ERR_INVALID_ARG), (dict(W=(1 << 30) + 64), b.TLIN_ERR_INVALID_ARG),   # beyond 32-bit tile arithmetic
+    (dict(kh_stride=(0, 0, 1 << 24)), b.TLIN_ERR_INVALID_ARG),                 # row stride of 32 MiB
     (dict(q_stride=(64 * 64 * 2, 64 * 64, 60)), b.TLIN_ERR_INVALID_ARG),       # row stride < D
     (dict(kh_stride=(1024 * 68 * 2, 1024 * 68, 68)), b.TLIN_ERR_INVALID_ARG),  # rows not 16-byte aligned
 ])
