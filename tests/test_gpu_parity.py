@@ -355,3 +355,68 @@ def test_errors_are_reported_not_raised_by_the_gpu():
     assert e.value.status == tl.binding.TLIN_ERR_INVALID_ARG
     with pytest.raises(ValueError):
         tl.tlin_history_attn(dev["Q"].cpu(), dev["Kh"], dev["Vh"])
+
+
+# ---------------------------------------------------------------- running maximum, streams, many heads
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+@pytest.mark.parametrize("direction", [1.0, -1.0])
+def test_scores_that_climb_or_fall_along_the_history(dtype, direction):
+    """Keys whose scores grow (or shrink) steadily with the row index, by 10 (fp32) or 300 (bf16)
+    powers of two over the history: the running maximum of the online softmax keeps moving (or never
+    moves after the first tile), partitions differ by more than the reference-point threshold (bf16:
+    by more than the fp32 exponent range), and almost all the weight sits on the rows at one end.
+    The fp32 span is kept small because the fp32 path rounds each score to about 1e-7 of its size
+    (times a few for the 128-term sum), which the exponential turns into that absolute error's worth
+    of relative error in the weight: at 21 nats the bound of 1e-5 is already reached (measured
+    1.2e-5), at 7 nats it is not; the fp32 kernel moves its reference point in every tile anyway."""
+    B, H, D, N, W = 1, 2, 128, 3000, 70
+    w = ti.Workload(f"climb_{dtype}_{direction}", B, H, D, N, W, dtype, 1.0, 8642)
+    host = ti.make(w)
+    rng = np.random.default_rng(5)
+    u = rng.standard_normal(D).astype(np.float32)
+    u /= np.linalg.norm(u)
+
+    def rounded(a):          # the generator's arrays are float32 for fp32 and bf16 bit patterns (uint16) for bf16
+        if dtype == ti.F32:
+            return a.astype(np.float32)
+        t = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16)
+        return t.view(torch.int16).numpy().view(host["Q"].dtype)
+
+    q = 4.0 * u[None, None, None, :] + 0.1 * rng.standard_normal((B, H, W, D))
+    ramp = direction * (np.arange(N, dtype=np.float64) / N)[None, None, :, None]
+    # scale * <q, k_j> = 4 * amp * ramp_j / sqrt(128) nats: 0.51 powers of two per unit of amp
+    amp = 20.0 if dtype == ti.F32 else 600.0
+    kh = amp * ramp * u[None, None, None, :] + 0.1 * rng.standard_normal((B, H, N, D))
+    host = dict(host, Q=rounded(q), Kh=rounded(kh))
+    dev = upload(host, dtype)
+    for s in (1, 4, 11):
+        o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, num_splits=s, return_lse=True)
+        ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], dtype, w.scale)
+        assert_close(o, ro, dtype, f"climb {direction} splits {s}")
+        np.testing.assert_allclose(to_host64(lse), rl, rtol=2e-6, atol=lse_atol(dtype, rl))
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], combine=mode, scale=w.scale)
+        ro = oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], dtype, w.scale, omode)
+        assert_close(o, ro, dtype, f"climb {direction} layer {mode}")
+
+
+def test_calls_on_a_stream_of_the_callers():
+    w = ti.Workload("stream", 1, 4, 128, 5000, 256, ti.BF16, 1.0, 1717)
+    host = ti.make(w)
+    dev = upload(host, w.dtype)
+    ro = oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        outs = [tl.tlin_layer_attn(*(dev[k] for k in ("Q", "Kh", "Vh", "Kw", "Vw")), scale=w.scale) for _ in range(3)]
+    side.synchronize()
+    for o in outs:
+        assert_close(o, ro, w.dtype, "side stream")
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+def test_many_small_heads(dtype):
+    # thousands of independent (batch, head) problems, each a fraction of a tile
+    w = ti.Workload(f"heads_{dtype}", 8, 300, 64, 100, 9, dtype, 1.0, 2323)
+    run_all(w, check_lse=True)
