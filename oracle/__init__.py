@@ -13,7 +13,9 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libtlin_oracle.so")
+# TLIN_ORACLE_LIB: a test hook.  tests/test_oracle_mutations.py points it at deliberately broken
+# builds of tlin_oracle.c to show that the pins notice them.
+_LIB_PATH = os.environ.get("TLIN_ORACLE_LIB") or os.path.join(_HERE, "libtlin_oracle.so")
 _lib = None
 
 F32, BF16 = 0, 1
