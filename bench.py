@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
-PEAK_F32_VALU_TFLOPS = 157.3
+PEAK_F32_MFMA_TFLOPS = 157.3    # MI355X dense fp32 matrix (the fp32 vector rate is the same figure)
 
 
 def parse():
@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--combine", choices=("sum", "joint"), default="sum")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--sweep", action="store_true", help="latency-vs-N sweep instead of the single workload")
-    ap.add_argument("--workload", choices=("config", "decode", "restore", "slide", "paper"), default="config",
+    ap.add_argument("--workload", choices=("config", "decode", "restore", "slide", "paper", "f32"), default="config",
                     help="config: --config's layer call (default). decode: the cache-hit step of Section 4.2, "
                          "--W newest rows (default 1) query --N history rows (default 131072) through "
                          "tlin_history_attn. restore: the context path's last layer, --N history rows (default "
@@ -48,7 +48,9 @@ def parse():
                          "sliding schedule of Section 5.1 over a sequence of --N rows (default 131072) in chunks of "
                          "--W rows (default 512) through tlin_slide_layer_attn. paper: the layer call at the paper's "
                          "own model shape, 12 heads of dimension 36, --W window rows (default 256; 1 = cache-hit "
-                         "step through tlin_history_attn) over --N history rows (default 131072)")
+                         "step through tlin_history_attn) over --N history rows (default 131072). f32: the layer call with fp32 "
+                         "inputs, 32 heads of dimension 128, --W window rows (default 512) over --N history rows "
+                         "(default 32768)")
     ap.add_argument("--N", type=int, default=None)
     ap.add_argument("--W", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -182,7 +184,7 @@ def main():
     if args.workload == "slide":
         return slide(args, ti, tl, binding, torch, np, combine)
 
-    layer = args.workload == "config" or (args.workload == "paper" and (args.W or 256) > 1)
+    layer = args.workload in ("config", "f32") or (args.workload == "paper" and (args.W or 256) > 1)
     if args.workload == "config":
         w = ti.config(args.config - 1)
         metric = "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak"
@@ -192,6 +194,10 @@ def main():
         metric = "attention of the paper's own model shape (12 heads x 36), bf16"
         what = ("tlin_layer_attn = history partitions + window causal + merge" if layer else
                 "tlin_history_attn = history partitions + merge (cache-hit step)")
+    elif args.workload == "f32":
+        w = ti.f32_point(args.N or 32768, args.W or 512)
+        metric = "layer call with fp32 inputs (fp32 matrix-core products); % fp32 MFMA peak"
+        what = "tlin_layer_attn = history partitions, window causal, merge"
     elif args.workload == "decode":
         w = ti.decode_point(args.N or 131072, args.W or 1)
         metric = "cache-hit step: newest rows x N-row history, bf16; % HBM peak"
@@ -263,13 +269,12 @@ def main():
     paired = layer and launches[0] > 0 and launches[1] == 0
     hist_tflops = (flops_h + (flops_w if paired else 0.0)) / (hist_ms * 1e-3) / 1e12
     hist_gbs = kv_bytes / (hist_ms * 1e-3) / 1e9
-    # Arithmetic intensity of the history kernel is W flop/byte (bf16): it is matrix-core bound
-    # when W exceeds the ridge point peak_flops/peak_bw, else HBM bound.  fp32 inputs use the
-    # vector ALUs.
-    if w.dtype == ti.F32:
-        roof = {"bound": "alu", "achieved": hist_tflops, "peak": PEAK_F32_VALU_TFLOPS, "unit": "TFLOP/s"}
-    elif flops_h / kv_bytes >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
-        roof = {"bound": "mfma", "achieved": hist_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s"}
+    # Arithmetic intensity of the history kernel is W flop/byte (bf16; W/2 for fp32): it is
+    # matrix-core bound when that exceeds the ridge point peak_flops/peak_bw of its operand type
+    # (fp32 inputs are multiplied by the fp32 matrix instructions), else HBM bound.
+    peak_mfma = PEAK_F32_MFMA_TFLOPS if w.dtype == ti.F32 else PEAK_BF16_MFMA_TFLOPS
+    if flops_h / kv_bytes >= peak_mfma * 1e12 / (PEAK_HBM_GBS * 1e9):
+        roof = {"bound": "mfma", "achieved": hist_tflops, "peak": peak_mfma, "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": hist_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
@@ -289,12 +294,12 @@ def main():
                    "combine": args.combine, "num_splits": binding.num_splits(tl.params_for(Q, w.N, num_splits=args.num_splits)),
                    "step": what, "kv_buffers_rotated": n_kv},
         "window_tokens_per_s": w.B * w.W / sec, "context_tokens_per_s": w.B * w.N / sec,
-        "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_MFMA_TFLOPS,
+        "pct_mfma_peak": 100.0 * tflops / peak_mfma,
         "step_GB_per_s": kv_bytes / sec / 1e9, "pct_hbm_peak": 100.0 * kv_bytes / sec / 1e9 / PEAK_HBM_GBS,
         "kernels_ms": {"history": hist_ms, "window_causal": win_ms, "merge": merge_ms},
         "roofline": roof,
     }
-    if roof["bound"] == "mfma" and not args.no_gemm_context:
+    if roof["bound"] == "mfma" and w.dtype != ti.F32 and not args.no_gemm_context:
         out["context"] = gemm_context(torch)
         if out["context"].get("library_bf16_gemm_TFLOPs"):
             out["context"]["kernel_vs_library_gemm"] = hist_tflops / out["context"]["library_bf16_gemm_TFLOPs"]

@@ -36,7 +36,8 @@
  *     dropout or key/value head sharing.  Non-finite inputs give unspecified outputs.
  *   - Results are exact softmax attention up to rounding: bf16 inputs are multiplied on the
  *     matrix cores with fp32 accumulation, softmax weights are rounded to bf16 before the
- *     second product; fp32 inputs use fp32 arithmetic throughout.
+ *     second product; fp32 inputs use fp32 arithmetic throughout (fp32 matrix instructions,
+ *     nothing is rounded below fp32).
  */
 #ifndef TLINATTN_H
 #define TLINATTN_H

@@ -19,7 +19,7 @@
 //   * V is stored row-major [key][d]; the A operand needs 4 consecutive keys at fixed d per
 //     lane, which is what ds_read_b64_tr_b16 returns (16 lanes read a 4x16 patch and get its
 //     transpose).  Two such reads form one 8-element operand.
-//   * K/V tiles of 64 keys go HBM -> LDS directly (global_load_lds_dwordx4: each wave
+//   * K/V tiles of 64 keys go HBM -> LDS directly (buffer_load_dwordx4 ... lds: each wave
 //     instruction moves 1 KB, lane i landing at base + 16*i) through a ring of NSTAGE tiles,
 //     the loads of the following tiles being in flight during compute.  One barrier per tile;
 //     completion is tracked by hand with s_waitcnt vmcnt.  (A compute unit keeps only some
@@ -30,9 +30,6 @@
 //     direct loads write LDS linearly, so the swizzle is applied on the source side: the lane
 //     that lands on chunk position c of row r fetches chunk c ^ swz(r) of that row.
 #pragma once
-#ifndef TLIN_BUFLOAD
-#define TLIN_BUFLOAD 1
-#endif
 #include "common.h"
 
 namespace tlin {
@@ -51,56 +48,10 @@ template <> struct Swz<64> {    // 128-byte rows, 8 chunks; two rows per 256-byt
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-// One wave-wide direct load: 64 lanes x 16 bytes from per-lane global addresses to the 1 KB of
-// LDS starting at the wave-uniform byte offset lds_base (lane i lands at lds_base + 16*i).
-// Issued through inline assembly on purpose: the compiler then does not know that LDS is
-// being written asynchronously and does not put a wait-for-all-loads in front of every LDS
-// read; completion is tracked explicitly with wait_vmcnt() before the tile's barrier.
-__device__ __forceinline__ void direct_load_1k(const char *gsrc, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_base), "v"(gsrc)
-                 : "memory", "m0");
-}
-
-// The same through a buffer descriptor: the tile's base address sits in scalar registers and a
-// lane contributes a 32-bit byte offset, which the address unit handles faster than 64-bit
-// per-lane addresses.  Offsets at or beyond `bytes` read as zeros (raw buffer, stride 0).
-__device__ __forceinline__ u32x4 tile_descriptor(const char *base, unsigned bytes)
-{
-    const uint64_t b = (uint64_t)base;
-    u32x4 d;
-    d[0] = __builtin_amdgcn_readfirstlane((unsigned)b);
-    d[1] = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32) & 0xffffu);   // stride 0, no swizzle
-    d[2] = __builtin_amdgcn_readfirstlane(bytes);
-    d[3] = 0x00020000u;                                                       // raw 32-bit data format
-    return d;
-}
-__device__ __forceinline__ void direct_load_1k(u32x4 desc, unsigned byte_off, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :
-                 : "s"(lds_base), "v"(byte_off), "s"(desc)
-                 : "memory", "m0");
-}
-
-__device__ __forceinline__ unsigned lds_offset(const char *p)
-{
-    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // RESIDENT: the whole key/value partition (at most NSTAGE tiles) is loaded into LDS once and the
 // workgroup then walks over query blocks qb, qb + q_groups, ... without any further barrier, so
 // its waves drift apart and one wave's matrix work overlaps another's softmax arithmetic.  Used
 // where the query side is the long one.
-extern __shared__ __attribute__((aligned(1024))) char tlin_smem[];   // the tile ring: 2 * NSTAGE * TILE_B bytes
 
 // The work of one workgroup; `bid` of `nblocks` is its index among the blocks of this problem set.
 // PAD: the tensors' head dimension a.D is smaller than the kernel's D.

@@ -168,6 +168,46 @@ __device__ __forceinline__ float xhalf_sum(float x)
     return lo + hi;
 }
 
+// One wave-wide direct load HBM -> LDS: 64 lanes x 16 bytes land on the 1 KB of LDS starting at
+// the wave-uniform byte offset lds_base (lane i at lds_base + 16*i).  The source is addressed
+// through a buffer descriptor: the tile's base address sits in scalar registers and a lane
+// contributes a 32-bit byte offset (the address unit handles those faster than 64-bit per-lane
+// addresses); offsets at or beyond the descriptor's size read as zeros (raw buffer, stride 0).
+// Issued through inline assembly on purpose: the compiler then does not know that LDS is
+// being written asynchronously and does not put a wait-for-all-loads in front of every LDS
+// read; completion is tracked explicitly with wait_vmcnt() before the tile's barrier.
+__device__ __forceinline__ u32x4 tile_descriptor(const char *base, unsigned bytes)
+{
+    const uint64_t b = (uint64_t)base;
+    u32x4 d;
+    d[0] = __builtin_amdgcn_readfirstlane((unsigned)b);
+    d[1] = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32) & 0xffffu);   // stride 0, no swizzle
+    d[2] = __builtin_amdgcn_readfirstlane(bytes);
+    d[3] = 0x00020000u;                                                       // raw 32-bit data format
+    return d;
+}
+__device__ __forceinline__ void direct_load_1k(u32x4 desc, unsigned byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(byte_off), "s"(desc)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ unsigned lds_offset(const char *p)
+{
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// The K/V tile ring of the attention kernels (dynamic LDS, sized by the launch).
+extern __shared__ __attribute__((aligned(1024))) char tlin_smem[];
+
 __device__ __forceinline__ unsigned short f32_to_bf16_bits(float f)
 {
     return __builtin_bit_cast(unsigned short, (__bf16)f);

@@ -36,13 +36,20 @@ Shape bf16_shape(int W)
 // treat the missing columns of Q as zeros and do not store the extra output columns.
 int dpad(int D) { return D <= 64 ? 64 : 128; }
 
-int key_tile(int in_dtype, int D) { return (in_dtype == TLIN_F32 && D == 128) ? 32 : 64; }
-int query_block(int in_dtype, int W) { return in_dtype == TLIN_F32 ? 32 : bf16_shape(W).bm(); }
+// Keys per tile: 32 KB of K and V per tile in both kernels.  Query rows per workgroup: the same
+// shapes for both input types.
+int key_tile(int in_dtype, int) { return in_dtype == TLIN_F32 ? 32 : 64; }
+int query_block(int, int W) { return bf16_shape(W).bm(); }
 
 // Workgroups the chip holds at once for a given kernel shape (LDS- and register-limited).
 int resident_wgs(int in_dtype, int W, int D)
 {
-    if (in_dtype == TLIN_F32) return kNumCU * 2;
+    if (in_dtype == TLIN_F32) {
+        // fp32 kernel: two waves per SIMD keep the matrix cores busy (8 waves per compute unit); its
+        // tile ring takes 64 KB of the 160 KB of LDS at D = 128 and 32 KB at D = 64
+        const int by_waves = 8 / bf16_shape(W).nw, by_lds = dpad(D) == 128 ? 2 : 4;
+        return kNumCU * (by_waves < by_lds ? by_waves : by_lds);
+    }
     // head dimension 64: tiles and register sets are half as large, three workgroups share a
     // compute unit (measured best for few heads); 128: eight- and two-wave workgroups fill a compute
     // unit alone (registers, LDS ring), two of the four-wave ones share it
@@ -168,8 +175,7 @@ Plan plan_history(const tlin_params *p)
         const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W) - 1) / query_block(p->in_dtype, p->W));
         const int64_t target = resident_wgs(p->in_dtype, p->W, p->D);
         want = (int)((target + base - 1) / base);
-        // (fp32 tiles are vector-ALU work and take several times longer: 4 are enough there)
-        const int min_tiles = p->in_dtype == TLIN_F32 ? 4 : 8;
+        const int min_tiles = 8;
         const int cap = ntiles / min_tiles > 1 ? ntiles / min_tiles : 1;
         if (want > cap) want = cap;
     }
@@ -277,6 +283,17 @@ tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
     return launch_bf16_shape<D, 2, 1, CAUSAL, CAUSAL ? 4 : 3>(a, grid, st);
 }
 
+// fp32 kernel: a ring of two 32-key tiles of K and V (64 KB at D = 128, no attribute needed).
+template <int D, bool CAUSAL>
+void launch_f32(const AttnArgs &a, Shape s, int grid, hipStream_t st)
+{
+    constexpr int lds_bytes = 2 * 2 * 32 * D * 4;
+    static_assert(lds_bytes <= 64 * 1024, "fp32 tile ring must fit the default dynamic LDS limit");
+    if (s.nw == 8) hipLaunchKernelGGL((attn_f32_kernel<D, 8, CAUSAL>), dim3(grid), dim3(512), lds_bytes, st, a);
+    else if (s.nw == 4) hipLaunchKernelGGL((attn_f32_kernel<D, 4, CAUSAL>), dim3(grid), dim3(256), lds_bytes, st, a);
+    else hipLaunchKernelGGL((attn_f32_kernel<D, 2, CAUSAL>), dim3(grid), dim3(128), lds_bytes, st, a);
+}
+
 // Key tiles the resident variant keeps in LDS (128 KB of keys and values).
 int resident_tiles(int D) { return D == 128 ? 4 : 8; }
 
@@ -321,12 +338,13 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
         else rc = causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
         if (rc != TLIN_OK) return rc;
     } else {
+        const Shape s = bf16_shape(p->W);
         if (dpad(p->D) == 128) {
-            if (causal) hipLaunchKernelGGL((attn_f32_kernel<128, true>), dim3(grid), dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((attn_f32_kernel<128, false>), dim3(grid), dim3(256), 0, st, a);
+            if (causal) launch_f32<128, true>(a, s, grid, st);
+            else launch_f32<128, false>(a, s, grid, st);
         } else {
-            if (causal) hipLaunchKernelGGL((attn_f32_kernel<64, true>), dim3(grid), dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((attn_f32_kernel<64, false>), dim3(grid), dim3(256), 0, st, a);
+            if (causal) launch_f32<64, true>(a, s, grid, st);
+            else launch_f32<64, false>(a, s, grid, st);
         }
     }
     return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;

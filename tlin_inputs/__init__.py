@@ -127,6 +127,12 @@ def paper_model_point(N: int, W: int = 256) -> Workload:
                     _BASE_SEED + 8 + 7919 * N + 104729 * W)
 
 
+def f32_point(N: int, W: int = 512) -> Workload:
+    """cfg4's shape with fp32 inputs (the precision of the paper's runs is not stated): what the
+    fp32 kernel sustains on a workload large enough to fill the chip."""
+    return Workload(f"f32_N{N}_W{W}", 1, 32, 128, N, W, F32, 1.0, _BASE_SEED + 9 + 7919 * N + 104729 * W)
+
+
 def degenerate_causal() -> Workload:
     """Empty history, window of 4096 rows: the layer reduces to standard causal attention."""
     return sweep_point(0, 4096)
