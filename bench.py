@@ -188,7 +188,7 @@ def main():
     if args.workload == "config":
         w = ti.config(args.config - 1)
         metric = "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak"
-        what = "tlin_layer_attn = history partitions + window causal (one launch for bf16) + merge"
+        what = "tlin_layer_attn = history partitions + window causal (one launch) + merge"
     elif args.workload == "paper":
         w = ti.paper_model_point(args.N or 131072, args.W or 256)
         metric = "attention of the paper's own model shape (12 heads x 36), bf16"
@@ -197,7 +197,7 @@ def main():
     elif args.workload == "f32":
         w = ti.f32_point(args.N or 32768, args.W or 512)
         metric = "layer call with fp32 inputs (fp32 matrix-core products); % fp32 MFMA peak"
-        what = "tlin_layer_attn = history partitions, window causal, merge"
+        what = "tlin_layer_attn = history partitions + window causal (one launch) + merge"
     elif args.workload == "decode":
         w = ti.decode_point(args.N or 131072, args.W or 1)
         metric = "cache-hit step: newest rows x N-row history, bf16; % HBM peak"
@@ -278,9 +278,9 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": hist_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["kernel"] = ("attn_f32_kernel (history partitions)" if w.dtype == ti.F32 else
-                      "attn_bf16_pair_kernel (history partitions + window blocks)" if paired else
-                      "attn_bf16_kernel (history partitions)")
+    kname = "attn_f32" if w.dtype == ti.F32 else "attn_bf16"
+    roof["kernel"] = (f"{kname}_pair_kernel (history partitions + window blocks)" if paired else
+                      f"{kname}_kernel (history partitions)")
     roof["kernel_ms"] = hist_ms
     roof["traffic"] = measured_traffic(w.name)
 

@@ -33,8 +33,9 @@ struct SwzF32 {
     static __device__ __forceinline__ int v(int r) { return ((r >> 2) & 1) << 3; }
 };
 
+// The work of one workgroup; `bid` of `nblocks` is its index among the blocks of this problem set.
 template <int D, int NW, bool CAUSAL>
-__global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a)
+__device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nblocks)
 {
     constexpr int BN = 32;                 // keys per tile
     constexpr int BM = NW * 32;            // query rows per workgroup
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
 
-    const int L = xcd_remap(blockIdx.x, gridDim.x);
+    const int L = xcd_remap(bid, nblocks);
     const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, a.nqb);
     if (pr.skip) return;                   // uniform over the workgroup
     const int qb = pr.qb, split = pr.split, bh = pr.bh;
@@ -279,6 +280,20 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a)
             a.Lpart[slot * a.W + row] = lt;
         }
     }
+}
+
+template <int D, int NW, bool CAUSAL>
+__global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a)
+{
+    attn_f32_body<D, NW, CAUSAL>(a, blockIdx.x, gridDim.x);
+}
+
+// History partition blocks and window causal blocks of one call in a single launch.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_f32_pair_kernel(const PairArgs f)
+{
+    if ((int)blockIdx.x < f.n_hist_blocks) attn_f32_body<D, NW, false>(f.hist, blockIdx.x, f.n_hist_blocks);
+    else attn_f32_body<D, NW, true>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
 }
 
 }  // namespace tlin

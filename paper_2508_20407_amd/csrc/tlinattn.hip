@@ -294,6 +294,17 @@ void launch_f32(const AttnArgs &a, Shape s, int grid, hipStream_t st)
     else hipLaunchKernelGGL((attn_f32_kernel<D, 2, CAUSAL>), dim3(grid), dim3(128), lds_bytes, st, a);
 }
 
+template <int D>
+tlin_status launch_f32_pair(const PairArgs &f, Shape s, hipStream_t st)
+{
+    constexpr int lds_bytes = 2 * 2 * 32 * D * 4;
+    const dim3 grid(f.n_hist_blocks + f.n_win_blocks);
+    if (s.nw == 8) hipLaunchKernelGGL((attn_f32_pair_kernel<D, 8>), grid, dim3(512), lds_bytes, st, f);
+    else if (s.nw == 4) hipLaunchKernelGGL((attn_f32_pair_kernel<D, 4>), grid, dim3(256), lds_bytes, st, f);
+    else hipLaunchKernelGGL((attn_f32_pair_kernel<D, 2>), grid, dim3(128), lds_bytes, st, f);
+    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+}
+
 // Key tiles the resident variant keeps in LDS (128 KB of keys and values).
 int resident_tiles(int D) { return D == 128 ? 4 : 8; }
 
@@ -443,14 +454,14 @@ tlin_status launch_pair_shape(const PairArgs &f, hipStream_t st)
     return launch_pair_shape_pad<D, NW, NSTAGE, false>(f, st);
 }
 
-// History partials and window partial of the same rows.  bf16: one launch for both problem sets.
+// History partials and window partial of the same rows: one launch for both problem sets.
 tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const AttnArgs &aw, hipStream_t hs)
 {
     const int qblk = query_block(p->in_dtype, p->W);
     const int nqb = (p->W + qblk - 1) / qblk;
     const int64_t per_set = (int64_t)p->B * p->H * nqb * (ah.nchunks ? ah.nchunks : 1);
     const int64_t nh = per_set * ah.nsplit, nw = per_set;
-    if (p->in_dtype == TLIN_BF16 && nh + nw <= 0x7fffffff) {
+    if (nh + nw <= 0x7fffffff) {
         PairArgs f = {};
         f.hist = ah;
         f.win = aw;
@@ -459,6 +470,7 @@ tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const Attn
         f.n_win_blocks = (int)nw;
         const Shape s = bf16_shape(p->W);
         LaunchTimer timer(KC_HISTORY, hs);
+        if (p->in_dtype == TLIN_F32) return dpad(p->D) == 128 ? launch_f32_pair<128>(f, s, hs) : launch_f32_pair<64>(f, s, hs);
         if (dpad(p->D) == 128) {
             if (s.nw == 8) return launch_pair_shape<128, 8, 2>(f, hs);
             if (s.nw == 4) return launch_pair_shape<128, 4, 2>(f, hs);
