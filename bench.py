@@ -53,6 +53,8 @@ def parse():
                          "(default 32768)")
     ap.add_argument("--N", type=int, default=None)
     ap.add_argument("--W", type=int, default=None)
+    ap.add_argument("--history-only", action="store_true",
+                    help="config / f32 / paper workloads: time tlin_history_attn alone instead of the layer call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemm-context", action="store_true",
                     help="skip the library bf16 GEMM timed after the steps (context figure for matrix-core-bound workloads)")
@@ -184,7 +186,7 @@ def main():
     if args.workload == "slide":
         return slide(args, ti, tl, binding, torch, np, combine)
 
-    layer = args.workload in ("config", "f32") or (args.workload == "paper" and (args.W or 256) > 1)
+    layer = (args.workload in ("config", "f32") or (args.workload == "paper" and (args.W or 256) > 1)) and not args.history_only
     if args.workload == "config":
         w = ti.config(args.config - 1)
         metric = "history-attention TFLOP/s & tokens/s at N=128K,W=512 bf16; % MFMA peak"
@@ -206,6 +208,8 @@ def main():
         w = ti.restore_point(args.N or 131072, args.W or 256)
         metric = "context-path restoration: N query rows x W_oh compressed rows, bf16"
         what = "tlin_history_attn, one partition"
+    if args.history_only:
+        what = "tlin_history_attn = history partitions + merge"
     host = ti.make(w) if layer else ti.make(w, which=("Q", "Kh", "Vh"))
     dev = upload(host, w.dtype, ti, torch, np)
     Q, Kh, Vh = dev["Q"], dev["Kh"], dev["Vh"]
