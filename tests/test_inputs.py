@@ -53,3 +53,12 @@ def test_workload_table():
     t = ti.make(small)
     assert t["Kh"].shape == (1, 1, 256, 128) and t["Q"].shape == (1, 1, 32, 128) and t["Kh"].dtype == np.uint16
     assert len(ti.sweep_points()) == 8 and ti.degenerate_causal().N == 0
+
+
+def test_points_after_the_fixed_configs():
+    d, r, p, f = ti.decode_point(131072, 1), ti.restore_point(131072, 256), ti.paper_model_point(1000000), ti.f32_point(32768)
+    assert (d.W, d.N, d.dtype) == (1, 131072, ti.BF16)
+    assert (r.W, r.N) == (131072, 256)                      # the query side is the long one
+    assert (p.H, p.D, p.W) == (12, 36, 256)                 # the paper's model: width 432 in 12 heads
+    assert (f.H, f.D, f.N, f.W, f.dtype) == (32, 128, 32768, 512, ti.F32)
+    assert len({w.seed for w in (d, r, p, f, ti.config(3))}) == 5
