@@ -16,7 +16,8 @@
 //               the B operand is that accumulator register as it stands (after the exponential),
 //               and the A operand is V[key 8g + 4h + e][32 db + j], one 4-byte LDS read.
 //   * K/V tiles of 32 keys go HBM -> LDS directly (1 KB per wave instruction) through a ring of
-//     two tiles, one barrier per tile, as in the bf16 kernel.  LDS rows are XOR-swizzled per
+//     two tiles, one barrier per tile, as in the bf16 kernel (two-wave workgroups: one tile, two
+//     barriers).  LDS rows are XOR-swizzled per
 //     16-byte chunk on the source side of the load: K chunk ^ (row & 15), so that the 16 lanes of a
 //     128-bit read cover all 64 banks; V chunk ^ 8 for rows with bit 2 set, so that the two
 //     half-waves (rows 4 apart, same columns) read different halves of the bank sweep.
@@ -45,7 +46,9 @@ __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nb
     constexpr int RPI = 1024 / ROWB;       // rows moved by one wave-wide direct load
     constexpr int NDMA = BN / RPI / NW;    // direct loads per wave per tensor per tile
     static_assert(BN % (RPI * NW) == 0 && NDMA >= 1, "tile does not divide over the waves");
-    constexpr int NSTAGE = 2;
+    // Two-wave workgroups (few query rows) keep a single tile in LDS, so that four of them share a
+    // compute unit and every SIMD has two waves: their loads are hidden by the other workgroups.
+    constexpr int NSTAGE = NW == 2 ? 1 : 2;
     constexpr int DT = D / 8;              // 16-byte operand fragments per row and half-wave
     constexpr int DB = D / 32;             // 32-row blocks of O^T
     static_assert(2 * NDMA < 64, "too many loads in flight for vmcnt");
@@ -146,8 +149,8 @@ __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nb
     for (int t = t0; t < t1w; ++t) {
         const int n = t - t0;
         wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();      // tile t is complete, and every wave has left tile t-1
-        if (t + 1 < t1) issue(t + 1, (n + 1) % NSTAGE);
+        __builtin_amdgcn_s_barrier();      // tile t is complete, and (two stages) every wave has left tile t-1
+        if (NSTAGE == 2 && t + 1 < t1) issue(t + 1, (n + 1) % NSTAGE);
         const int key0 = t * BN;
         const char *Kt = Ks + (n % NSTAGE) * TILE_B;
         const char *Vt = Vs + (n % NSTAGE) * TILE_B;
@@ -229,12 +232,20 @@ __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nb
             for (int v = 0; v < 16; ++v) oacc[db][v] += pv[v];
             __builtin_amdgcn_sched_barrier(0);     // keeps the next block's V reads (registers) behind this block
         }
+        if (NSTAGE == 1 && t + 1 < t1) {
+            __builtin_amdgcn_s_barrier();          // every wave has left the tile that is overwritten now
+            issue(t + 1, 0);
+        }
     }
 
     for (int t = t1w; CAUSAL && t < t1; ++t) {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (t + 1 < t1) issue(t + 1, (t - t0 + 1) % NSTAGE);
+        if (NSTAGE == 2 && t + 1 < t1) issue(t + 1, (t - t0 + 1) % NSTAGE);
+        if (NSTAGE == 1 && t + 1 < t1) {
+            __builtin_amdgcn_s_barrier();
+            issue(t + 1, 0);
+        }
     }
 
     // ---- epilogue.  Accumulator register v of block db is d = 32*db + 8*(v/4) + 4*h + v%4.

@@ -46,8 +46,10 @@ int resident_wgs(int in_dtype, int W, int D)
 {
     if (in_dtype == TLIN_F32) {
         // fp32 kernel: two waves per SIMD keep the matrix cores busy (8 waves per compute unit); its
-        // tile ring takes 64 KB of the 160 KB of LDS at D = 128 and 32 KB at D = 64
-        const int by_waves = 8 / bf16_shape(W).nw, by_lds = dpad(D) == 128 ? 2 : 4;
+        // tile ring takes 64 KB of the 160 KB of LDS at D = 128 and 32 KB at D = 64 (half of that in
+        // the two-wave shape)
+        const int nw = bf16_shape(W).nw;
+        const int by_waves = 8 / nw, by_lds = (dpad(D) == 128 ? 2 : 4) * (nw == 2 ? 2 : 1);
         return kNumCU * (by_waves < by_lds ? by_waves : by_lds);
     }
     // head dimension 64: tiles and register sets are half as large, three workgroups share a
@@ -287,11 +289,11 @@ tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 template <int D, bool CAUSAL>
 void launch_f32(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    constexpr int lds_bytes = 2 * 2 * 32 * D * 4;
+    constexpr int lds_bytes = 2 * 2 * 32 * D * 4;    // the two-wave shape keeps one tile: half of it
     static_assert(lds_bytes <= 64 * 1024, "fp32 tile ring must fit the default dynamic LDS limit");
     if (s.nw == 8) hipLaunchKernelGGL((attn_f32_kernel<D, 8, CAUSAL>), dim3(grid), dim3(512), lds_bytes, st, a);
     else if (s.nw == 4) hipLaunchKernelGGL((attn_f32_kernel<D, 4, CAUSAL>), dim3(grid), dim3(256), lds_bytes, st, a);
-    else hipLaunchKernelGGL((attn_f32_kernel<D, 2, CAUSAL>), dim3(grid), dim3(128), lds_bytes, st, a);
+    else hipLaunchKernelGGL((attn_f32_kernel<D, 2, CAUSAL>), dim3(grid), dim3(128), lds_bytes / 2, st, a);
 }
 
 template <int D>
@@ -301,7 +303,7 @@ tlin_status launch_f32_pair(const PairArgs &f, Shape s, hipStream_t st)
     const dim3 grid(f.n_hist_blocks + f.n_win_blocks);
     if (s.nw == 8) hipLaunchKernelGGL((attn_f32_pair_kernel<D, 8>), grid, dim3(512), lds_bytes, st, f);
     else if (s.nw == 4) hipLaunchKernelGGL((attn_f32_pair_kernel<D, 4>), grid, dim3(256), lds_bytes, st, f);
-    else hipLaunchKernelGGL((attn_f32_pair_kernel<D, 2>), grid, dim3(128), lds_bytes, st, f);
+    else hipLaunchKernelGGL((attn_f32_pair_kernel<D, 2>), grid, dim3(128), lds_bytes / 2, st, f);
     return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
 }
 
