@@ -53,10 +53,10 @@ int resident_wgs(int in_dtype, int W, int D)
         return kNumCU * (by_waves < by_lds ? by_waves : by_lds);
     }
     // head dimension 64: tiles and register sets are half as large, three workgroups share a
-    // compute unit (measured best for few heads); 128: eight- and two-wave workgroups fill a compute
-    // unit alone (registers, LDS ring), two of the four-wave ones share it
+    // compute unit (measured best for few heads); 128: an eight-wave workgroup fills a compute unit
+    // alone (registers), two of the smaller ones share it (two-tile LDS ring of 64 KB each)
     if (dpad(D) == 64) return kNumCU * 3;
-    return kNumCU * (bf16_shape(W).nw == 4 ? 2 : 1);
+    return kNumCU * (bf16_shape(W).nw == 8 ? 1 : 2);
 }
 
 // ---- measurement aid: per-kernel timing with HIP events on the launch stream
@@ -280,9 +280,10 @@ tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
 template <int D, bool CAUSAL>
 tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, CAUSAL ? 4 : 2>(a, grid, st);
-    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, CAUSAL ? 4 : 2>(a, grid, st);
-    return launch_bf16_shape<D, 2, 1, CAUSAL, CAUSAL ? 4 : 3>(a, grid, st);
+    constexpr int NS = CAUSAL ? 4 : 2;
+    if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, NS>(a, grid, st);
+    if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, NS>(a, grid, st);
+    return launch_bf16_shape<D, 2, 1, CAUSAL, NS>(a, grid, st);
 }
 
 // fp32 kernel: a ring of two 32-key tiles of K and V (64 KB at D = 128, no attribute needed).
