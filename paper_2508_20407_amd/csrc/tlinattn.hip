@@ -477,7 +477,7 @@ tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const Attn
         if (dpad(p->D) == 128) {
             if (s.nw == 8) return launch_pair_shape<128, 8, 2>(f, hs);
             if (s.nw == 4) return launch_pair_shape<128, 4, 2>(f, hs);
-            return launch_pair_shape<128, 2, 3>(f, hs);
+            return launch_pair_shape<128, 2, 2>(f, hs);
         }
         if (s.nw == 8) return launch_pair_shape<64, 8, 2>(f, hs);
         if (s.nw == 4) return launch_pair_shape<64, 4, 2>(f, hs);
