@@ -420,3 +420,28 @@ def test_many_small_heads(dtype):
     # thousands of independent (batch, head) problems, each a fraction of a tile
     w = ti.Workload(f"heads_{dtype}", 8, 300, 64, 100, 9, dtype, 1.0, 2323)
     run_all(w, check_lse=True)
+
+
+def test_bf16_output_for_fp32_inputs():
+    """fp32 arithmetic, result rounded to bf16 at the store: within half a unit in the last place of
+    bf16 (8 significant bits: relative 2^-8) plus the fp32 path's own bound, for the direct, merged
+    and layer paths."""
+    w = ti.Workload("f32_bf16out", 1, 3, 128, 1500, 200, ti.F32, 1.0, 6161)
+    host = ti.make(w)
+    dev = upload(host, w.dtype)
+    Q, Kh, Vh, Kw, Vw = (dev[k] for k in ("Q", "Kh", "Vh", "Kw", "Vw"))
+
+    def check(o, ref, what):
+        assert o.dtype == torch.bfloat16
+        g = to_host64(o)
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        err = np.abs(g - ref) / np.maximum(np.abs(ref), rms)
+        assert err.max() <= 2.0 ** -8 + 1e-5, f"{what}: {err.max():.3e}"
+
+    for s in (1, 5):
+        o = tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale, num_splits=s, out_dtype=torch.bfloat16)
+        check(o, oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)[0], f"history splits {s}")
+    o = tl.tlin_window_causal_attn(Q, Kw, Vw, scale=w.scale, out_dtype=torch.bfloat16)
+    check(o, oracle.window_causal(host["Q"], host["Kw"], host["Vw"], w.dtype, w.scale)[0], "window")
+    o = tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=tl.TLIN_COMBINE_JOINT, scale=w.scale, out_dtype=torch.bfloat16)
+    check(o, oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.JOINT), "layer")
