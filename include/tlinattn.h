@@ -29,7 +29,9 @@
  *     of the last piece is ignored; in O those elements are left untouched.
  *   - Calls enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and return without synchronising.  Calls using the same workspace must be ordered on
- *     one stream.
+ *     one stream.  Nothing else is enqueued (no copies, no memsets), so a call can be captured
+ *     into a HIP graph once the same call shape has run once outside a capture on that device
+ *     (the first launch of a kernel raises its LDS limit, which is not a stream operation).
  *   - Errors are reported by return code only.  Argument validation runs on the host before
  *     any HIP call, so it behaves the same on a machine without a GPU.
  *   - Each (b, h) is an independent attention problem; there is no positional term, bias,

@@ -445,3 +445,43 @@ def test_bf16_output_for_fp32_inputs():
     check(o, oracle.window_causal(host["Q"], host["Kw"], host["Vw"], w.dtype, w.scale)[0], "window")
     o = tl.tlin_layer_attn(Q, Kh, Vh, Kw, Vw, combine=tl.TLIN_COMBINE_JOINT, scale=w.scale, out_dtype=torch.bfloat16)
     check(o, oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.JOINT), "layer")
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+def test_layer_call_replays_from_a_hip_graph(dtype):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a call can be captured into a HIP graph once its one-time set-up has run.
+    The graph is replayed several times with new inputs written into the captured tensors and eager
+    work in between; every replay must equal the eager call on the same inputs, and the oracle."""
+    w = ti.Workload(f"graph_{dtype}", 2, 4, 128, 3000, 160, dtype, 1.0, 7373)
+    names = ("Q", "Kh", "Vh", "Kw", "Vw")
+    hosts = [ti.make(ti.Workload(w.name, w.B, w.H, w.D, w.N, w.W, dtype, 1.0, w.seed + i)) for i in range(3)]
+    devs = [upload(h, dtype) for h in hosts]
+    static = {k: devs[0][k].clone() for k in names}
+    ws = tl.Workspace()
+
+    def call(t):
+        return tl.tlin_layer_attn(*(t[k] for k in names), combine=tl.TLIN_COMBINE_JOINT, scale=w.scale, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(static)                                   # one-time set-up and workspace allocation, outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = call(static)
+    for rep in range(5):
+        i = rep % 3
+        for k in names:
+            static[k].copy_(devs[i][k])
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        eager = call(devs[i])                          # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager), f"replay {rep} differs from the eager call"
+        if rep < 3:
+            ro = oracle.layer(*(hosts[i][k] for k in names), dtype, w.scale, oracle.JOINT)
+            assert_close(got, ro, dtype, f"graph replay {rep}")
