@@ -177,7 +177,9 @@ Plan plan_history(const tlin_params *p)
         const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W) - 1) / query_block(p->in_dtype, p->W));
         const int64_t target = resident_wgs(p->in_dtype, p->W, p->D);
         want = (int)((target + base - 1) / base);
-        const int min_tiles = 8;
+        // (a handful of (head, query block) items cannot fill the chip anyway: there the partials
+        // are few in total and short partitions pay)
+        const int min_tiles = base <= 4 ? 2 : 8;
         const int cap = ntiles / min_tiles > 1 ? ntiles / min_tiles : 1;
         if (want > cap) want = cap;
     }
