@@ -149,7 +149,8 @@ tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const voi
 tlin_status tlin_profile_enable(int32_t enable);
 tlin_status tlin_profile_read(double ms[3], int64_t launches[3]);
 
-const char *tlin_status_string(tlin_status s);
+/* Text for a tlin_status value; any other integer gives "unknown status". */
+const char *tlin_status_string(int status);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int32_t tlin_version(void);

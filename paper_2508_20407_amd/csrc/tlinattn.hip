@@ -672,9 +672,9 @@ tlin_status tlin_profile_read(double ms[3], int64_t launches[3])
     return rc;
 }
 
-const char *tlin_status_string(tlin_status s)
+const char *tlin_status_string(int status)
 {
-    switch (s) {
+    switch (status) {
     case TLIN_OK: return "ok";
     case TLIN_ERR_INVALID_ARG: return "invalid argument";
     case TLIN_ERR_UNSUPPORTED: return "unsupported head dimension or dtype";
