@@ -485,3 +485,23 @@ def test_layer_call_replays_from_a_hip_graph(dtype):
         if rep < 3:
             ro = oracle.layer(*(hosts[i][k] for k in names), dtype, w.scale, oracle.JOINT)
             assert_close(got, ro, dtype, f"graph replay {rep}")
+
+
+@pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
+def test_slide_on_interleaved_head_layout(dtype):
+    """The sliding schedule on tensors stored [B, L, H, D] (what a fused projection writes) and
+    viewed as [B, H, L, D]: head stride D, row stride H*D; K and V of both roles are one tensor each."""
+    B, H, L, D, chunk = 2, 3, 700, 64, 96
+    w = ti.Workload(f"slide_strided_{dtype}", B, H, D, L, chunk, dtype, 1.0, 9191)
+    shape = (B, H, L, D)
+    host = {n: ti.normal(shape, dtype, w.seed, tag, w.mul) for n, tag in (("Q", ti.TAG_Q), ("K", ti.TAG_KH), ("V", ti.TAG_VH))}
+    dev = upload(host, dtype)
+
+    def interleave(t):
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Q, K, V = (interleave(dev[k]) for k in ("Q", "K", "V"))
+    assert not Q.is_contiguous()
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_slide_layer_attn(Q, K, V, K, V, chunk, combine=mode, scale=w.scale)
+        ro = oracle.slide(host["Q"], host["K"], host["V"], host["K"], host["V"], dtype, w.scale, chunk, omode)
+        assert_close(o, ro, dtype, f"strided slide mode {mode}")
