@@ -40,6 +40,12 @@
  *     matrix cores with fp32 accumulation, softmax weights are rounded to bf16 before the
  *     second product; fp32 inputs use fp32 arithmetic throughout (fp32 matrix instructions,
  *     nothing is rounded below fp32).
+ *   - Accuracy envelope.  bf16 inputs: |O - exact| <= 2e-2 (mean <= 5e-3) for inputs of unit
+ *     scale.  fp32 inputs: a logit is an fp32 sum of D products and carries an absolute error of
+ *     a few 2^-24 of its own size, which the exponential turns into the same RELATIVE error of
+ *     the weight; the result is within 1e-5 of the exact one, relative to max(|O|, rms(O)),
+ *     while the logits scale * <q, k> stay within about 10 nats in magnitude, and within 1e-6 per
+ *     nat of logit magnitude beyond that.
  */
 #ifndef TLINATTN_H
 #define TLINATTN_H
@@ -54,9 +60,11 @@ extern "C" {
 typedef enum {
     TLIN_OK = 0,
     TLIN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad stride/alignment/scale */
-    TLIN_ERR_UNSUPPORTED = 2, /* head dimension or dtype combination not implemented */
+    TLIN_ERR_UNSUPPORTED = 2, /* head dimension or dtype combination not implemented, or the current
+                                 device is not an MI355X (gfx950 with 256 compute units) */
     TLIN_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or smaller than required */
-    TLIN_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed */
+    TLIN_ERR_HIP = 4          /* a HIP runtime call or kernel launch of this call failed (errors left
+                                 behind by the caller's earlier work are neither reported nor cleared) */
 } tlin_status;
 
 typedef enum { TLIN_F32 = 0, TLIN_BF16 = 1 } tlin_dtype;
@@ -138,16 +146,6 @@ size_t tlin_slide_workspace_bytes(const tlin_params *p);
 tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const void *K_hist,
                                   const void *V_hist, const void *K_win, const void *V_win, void *O,
                                   void *ws, size_t ws_bytes, void *stream);
-
-/* Measurement aid (not part of the attention path).  While enabled, every kernel the library
- * launches is bracketed by a pair of HIP events recorded on the launch stream.
- * tlin_profile_read waits for the recorded events, returns the summed durations in
- * milliseconds and the launch counts per kernel class - [0] history partition kernel,
- * [1] window causal kernel, [2] merge kernel - and clears the record.  The event objects are
- * created by the library on first use and kept for reuse.  Intended for benchmarks; leave it
- * off otherwise. */
-tlin_status tlin_profile_enable(int32_t enable);
-tlin_status tlin_profile_read(double ms[3], int64_t launches[3]);
 
 /* Text for a tlin_status value; any other integer gives "unknown status". */
 const char *tlin_status_string(int status);

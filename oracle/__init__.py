@@ -13,9 +13,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# TLIN_ORACLE_LIB: a test hook.  tests/test_oracle_mutations.py points it at deliberately broken
-# builds of tlin_oracle.c to show that the pins notice them.
-_LIB_PATH = os.environ.get("TLIN_ORACLE_LIB") or os.path.join(_HERE, "libtlin_oracle.so")
+_LIB_PATH = os.path.join(_HERE, "libtlin_oracle.so")
 _lib = None
 
 F32, BF16 = 0, 1
@@ -32,6 +30,17 @@ def build(verbose: bool = False) -> str:
     global _lib
     _lib = None
     return _LIB_PATH
+
+
+def use_library(path: str) -> None:
+    """Load another build of tlin_oracle.c instead of the one next to this file.  Only the pin
+    tests call this (through their --oracle-lib option, which the GPU tests refuse): the
+    mutation test points them at deliberately broken builds to show that the pins notice."""
+    global _lib, _LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(path)
+    _LIB_PATH = path
+    _lib = None
 
 
 def _load():

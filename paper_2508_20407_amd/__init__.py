@@ -61,16 +61,31 @@ class Workspace:
         self.buf = None
 
     def get(self, nbytes: int, device):
+        """(256-byte aligned address, bytes) of a region of at least nbytes inside the buffer."""
         torch = _torch()
         if nbytes == 0:
             return 0, 0
-        if self.buf is None or self.buf.numel() < nbytes or self.buf.device != device:
-            self.buf = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
-        addr = (self.buf.data_ptr() + 255) // 256 * 256
-        return addr, nbytes
+        if self.buf is not None and self.buf.device == device:
+            addr = (self.buf.data_ptr() + 255) // 256 * 256
+            if self.buf.data_ptr() + self.buf.numel() - addr >= nbytes:      # capacity behind the aligned address
+                return addr, nbytes
+        self.buf = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        return (self.buf.data_ptr() + 255) // 256 * 256, nbytes
 
 
-_default_ws = Workspace()
+# Calls that share a workspace must be ordered on one stream, so the workspaces the wrappers
+# fall back to are kept per (device, stream).
+_default_ws = {}
+
+
+def _workspace_for(t, workspace):
+    if workspace is not None:
+        return workspace
+    key = (t.device, _stream(t))
+    ws = _default_ws.get(key)
+    if ws is None:
+        ws = _default_ws[key] = Workspace()
+    return ws
 
 
 def _stream(t):
@@ -95,7 +110,7 @@ def tlin_history_attn(q_win, k_hist, v_hist, *, scale=None, out_dtype=None, num_
     o = _out(q_win, out_dtype)
     p = params_for(q_win, k_hist.shape[2], o.dtype, scale, num_splits, kh=k_hist, vh=v_hist, o=o)
     lse = torch.empty(q_win.shape[:3], dtype=torch.float32, device=q_win.device) if return_lse else None
-    ws, nb = (workspace or _default_ws).get(binding.workspace_bytes(p), q_win.device)
+    ws, nb = _workspace_for(q_win, workspace).get(binding.workspace_bytes(p), q_win.device)
     st = binding.history_attn_raw(p, q_win.data_ptr(), k_hist.data_ptr(), v_hist.data_ptr(), o.data_ptr(),
                                   lse.data_ptr() if return_lse else None, ws or None, nb, _stream(q_win))
     binding._check(st, "tlin_history_attn")
@@ -123,7 +138,7 @@ def tlin_layer_attn(q_win, k_hist, v_hist, k_win, v_win, *, combine=TLIN_COMBINE
     o = _out(q_win, out_dtype)
     p = params_for(q_win, n, o.dtype, scale, num_splits, combine,
                    kh=k_hist if n else None, vh=v_hist if n else None, kw=k_win, vw=v_win, o=o)
-    ws, nb = (workspace or _default_ws).get(binding.workspace_bytes(p), q_win.device)
+    ws, nb = _workspace_for(q_win, workspace).get(binding.workspace_bytes(p), q_win.device)
     st = binding.layer_attn_raw(p, q_win.data_ptr(), k_hist.data_ptr() if n else None,
                                 v_hist.data_ptr() if n else None, k_win.data_ptr(), v_win.data_ptr(),
                                 o.data_ptr(), ws or None, nb, _stream(q_win))
@@ -146,7 +161,7 @@ def tlin_slide_layer_attn(q, k_hist, v_hist, k_win, v_win, chunk, *, combine=TLI
     p = binding.make_params(B, H, int(chunk), L, D, code, oc, (D ** -0.5) if scale is None else scale, num_splits,
                             combine, q_stride=_strides(q), kh_stride=_strides(k_hist), vh_stride=_strides(v_hist),
                             kw_stride=_strides(k_win), vw_stride=_strides(v_win), o_stride=_strides(o))
-    ws, nb = (workspace or _default_ws).get(binding.slide_workspace_bytes(p), q.device)
+    ws, nb = _workspace_for(q, workspace).get(binding.slide_workspace_bytes(p), q.device)
     st = binding.slide_layer_attn_raw(p, q.data_ptr(), k_hist.data_ptr(), v_hist.data_ptr(), k_win.data_ptr(),
                                       v_win.data_ptr(), o.data_ptr(), ws or None, nb, _stream(q))
     binding._check(st, "tlin_slide_layer_attn")

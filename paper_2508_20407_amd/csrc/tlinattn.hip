@@ -1,8 +1,10 @@
 // libtlinattn: C-ABI entry points (see include/tlinattn.h), argument validation, partition
 // planning and kernel launches.  gfx950 only.
 #include "tlinattn.h"
+#include "tlinattn_profile.h"
 
 #include <math.h>
+#include <string.h>
 
 #include <atomic>
 #include <mutex>
@@ -17,8 +19,37 @@ using namespace tlin;
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 constexpr int kMaxRows = 1 << 30;
+
+// One kernel launch, reporting the status of this launch only: errors that the caller's earlier
+// work left behind stay where they are (nothing here reads or clears the runtime's last error).
+// Every kernel of the library takes a single argument structure by value.
+template <typename Args>
+tlin_status launch_kernel(const void *kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, const Args &a)
+{
+    void *argv[] = {const_cast<Args *>(&a)};
+    return hipLaunchKernel(kernel, grid, block, argv, lds_bytes, st) == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+}
+
+// The kernels and the partition planning are written for MI355X: gfx950, 256 compute units in 8
+// XCDs (kNumCU, kNumXCD).  Checked once per device ordinal, after argument validation and before
+// the first launch on that device.
+tlin_status check_device()
+{
+    static std::atomic<uint64_t> good{0}, bad{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return TLIN_ERR_HIP;
+    if (dev < 0 || dev >= 64) return TLIN_ERR_UNSUPPORTED;
+    const uint64_t bit = (uint64_t)1 << dev;
+    if (good.load(std::memory_order_acquire) & bit) return TLIN_OK;
+    if (bad.load(std::memory_order_acquire) & bit) return TLIN_ERR_UNSUPPORTED;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return TLIN_ERR_HIP;
+    const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0 && prop.multiProcessorCount == kNumCU;
+    (ok ? good : bad).fetch_or(bit, std::memory_order_release);
+    return ok ? TLIN_OK : TLIN_ERR_UNSUPPORTED;
+}
 
 struct Strides { int64_t b, h, r; };
 
@@ -263,8 +294,7 @@ tlin_status launch_bf16_shape_pad(const AttnArgs &a, int grid, hipStream_t st)
     auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
-    return TLIN_OK;
+    return launch_kernel((const void *)kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
 }
 
 // The variant with a.D below the kernel's D is a kernel of its own, so that the exact sizes carry
@@ -290,13 +320,13 @@ tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 
 // fp32 kernel: a ring of two 32-key tiles of K and V (64 KB at D = 128, no attribute needed).
 template <int D, bool CAUSAL>
-void launch_f32(const AttnArgs &a, Shape s, int grid, hipStream_t st)
+tlin_status launch_f32(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * 2 * 32 * D * 4;    // the two-wave shape keeps one tile: half of it
     static_assert(lds_bytes <= 64 * 1024, "fp32 tile ring must fit the default dynamic LDS limit");
-    if (s.nw == 8) hipLaunchKernelGGL((attn_f32_kernel<D, 8, CAUSAL>), dim3(grid), dim3(512), lds_bytes, st, a);
-    else if (s.nw == 4) hipLaunchKernelGGL((attn_f32_kernel<D, 4, CAUSAL>), dim3(grid), dim3(256), lds_bytes, st, a);
-    else hipLaunchKernelGGL((attn_f32_kernel<D, 2, CAUSAL>), dim3(grid), dim3(128), lds_bytes / 2, st, a);
+    if (s.nw == 8) return launch_kernel((const void *)attn_f32_kernel<D, 8, CAUSAL>, dim3(grid), dim3(512), lds_bytes, st, a);
+    if (s.nw == 4) return launch_kernel((const void *)attn_f32_kernel<D, 4, CAUSAL>, dim3(grid), dim3(256), lds_bytes, st, a);
+    return launch_kernel((const void *)attn_f32_kernel<D, 2, CAUSAL>, dim3(grid), dim3(128), lds_bytes / 2, st, a);
 }
 
 template <int D>
@@ -304,10 +334,9 @@ tlin_status launch_f32_pair(const PairArgs &f, Shape s, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * 2 * 32 * D * 4;
     const dim3 grid(f.n_hist_blocks + f.n_win_blocks);
-    if (s.nw == 8) hipLaunchKernelGGL((attn_f32_pair_kernel<D, 8>), grid, dim3(512), lds_bytes, st, f);
-    else if (s.nw == 4) hipLaunchKernelGGL((attn_f32_pair_kernel<D, 4>), grid, dim3(256), lds_bytes, st, f);
-    else hipLaunchKernelGGL((attn_f32_pair_kernel<D, 2>), grid, dim3(128), lds_bytes / 2, st, f);
-    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+    if (s.nw == 8) return launch_kernel((const void *)attn_f32_pair_kernel<D, 8>, grid, dim3(512), lds_bytes, st, f);
+    if (s.nw == 4) return launch_kernel((const void *)attn_f32_pair_kernel<D, 4>, grid, dim3(256), lds_bytes, st, f);
+    return launch_kernel((const void *)attn_f32_pair_kernel<D, 2>, grid, dim3(128), lds_bytes / 2, st, f);
 }
 
 // Key tiles the resident variant keeps in LDS (128 KB of keys and values).
@@ -338,32 +367,20 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
         const int64_t grid64 = bh * g;
         if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
         LaunchTimer timer(KC_HISTORY, st);
-        const tlin_status rc = dpad(p->D) == 128 ? launch_bf16_shape<128, 8, 1, false, 4, true>(a, (int)grid64, st)
-                                           : launch_bf16_shape<64, 8, 1, false, 8, true>(a, (int)grid64, st);
-        if (rc != TLIN_OK) return rc;
-        return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+        return dpad(p->D) == 128 ? launch_bf16_shape<128, 8, 1, false, 4, true>(a, (int)grid64, st)
+                                 : launch_bf16_shape<64, 8, 1, false, 8, true>(a, (int)grid64, st);
     }
     const int64_t grid64 = (int64_t)p->B * p->H * a.nqb * a.nsplit * (a.nchunks ? a.nchunks : 1);
     if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     const int grid = (int)grid64;
     LaunchTimer timer(causal ? KC_WINDOW : KC_HISTORY, st);
+    const Shape s = bf16_shape(p->W);
     if (p->in_dtype == TLIN_BF16) {
-        const Shape s = bf16_shape(p->W);
-        tlin_status rc;
-        if (dpad(p->D) == 128) rc = causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
-        else rc = causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
-        if (rc != TLIN_OK) return rc;
-    } else {
-        const Shape s = bf16_shape(p->W);
-        if (dpad(p->D) == 128) {
-            if (causal) launch_f32<128, true>(a, s, grid, st);
-            else launch_f32<128, false>(a, s, grid, st);
-        } else {
-            if (causal) launch_f32<64, true>(a, s, grid, st);
-            else launch_f32<64, false>(a, s, grid, st);
-        }
+        if (dpad(p->D) == 128) return causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
+        return causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
     }
-    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+    if (dpad(p->D) == 128) return causal ? launch_f32<128, true>(a, s, grid, st) : launch_f32<128, false>(a, s, grid, st);
+    return causal ? launch_f32<64, true>(a, s, grid, st) : launch_f32<64, false>(a, s, grid, st);
 }
 
 tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
@@ -381,16 +398,10 @@ tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
     const int rpb = 256 / (dpad(p->D) / 4 * sl);
     const int grid = (int)((total + rpb - 1) / rpb);
     LaunchTimer timer(KC_MERGE, st);
-    if (dpad(p->D) == 128) {
-        if (sl == 8) hipLaunchKernelGGL((merge_kernel<128, 8>), dim3(grid), dim3(256), 0, st, m);
-        else if (sl == 4) hipLaunchKernelGGL((merge_kernel<128, 4>), dim3(grid), dim3(256), 0, st, m);
-        else hipLaunchKernelGGL((merge_kernel<128, 1>), dim3(grid), dim3(256), 0, st, m);
-    } else {
-        if (sl == 8) hipLaunchKernelGGL((merge_kernel<64, 8>), dim3(grid), dim3(256), 0, st, m);
-        else if (sl == 4) hipLaunchKernelGGL((merge_kernel<64, 4>), dim3(grid), dim3(256), 0, st, m);
-        else hipLaunchKernelGGL((merge_kernel<64, 1>), dim3(grid), dim3(256), 0, st, m);
-    }
-    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+    const void *kernel;
+    if (dpad(p->D) == 128) kernel = sl == 8 ? (const void *)merge_kernel<128, 8> : sl == 4 ? (const void *)merge_kernel<128, 4> : (const void *)merge_kernel<128, 1>;
+    else kernel = sl == 8 ? (const void *)merge_kernel<64, 8> : sl == 4 ? (const void *)merge_kernel<64, 4> : (const void *)merge_kernel<64, 1>;
+    return launch_kernel(kernel, dim3(grid), dim3(256), 0, st, m);
 }
 
 AttnArgs base_args(const tlin_params *p, const void *Q, const void *K, const void *V, const int64_t ks[3],
@@ -448,8 +459,7 @@ tlin_status launch_pair_shape_pad(const PairArgs &f, hipStream_t st)
     auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE, PAD>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
-    hipLaunchKernelGGL(kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
-    return hipGetLastError() == hipSuccess ? TLIN_OK : TLIN_ERR_HIP;
+    return launch_kernel((const void *)kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
 }
 
 template <int D, int NW, int NSTAGE>
@@ -497,6 +507,46 @@ tlin_status check_ws(const void *ws, size_t have, size_t need)
     return TLIN_OK;
 }
 
+// Argument checks of the layer call (host only).
+tlin_status check_layer_args(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
+                             const void *K_win, const void *V_win, const void *O)
+{
+    tlin_status st = check_common(p, true, true);
+    if (st) return st;
+    if ((st = check_dense_rows(p, T_Q | T_KW | T_VW | T_O | (p->N > 0 ? T_KH | T_VH : 0)))) return st;
+    if (p->combine != TLIN_COMBINE_SUM && p->combine != TLIN_COMBINE_JOINT) return TLIN_ERR_INVALID_ARG;
+    if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
+    if (p->N > 0 && (!K_hist || !V_hist)) return TLIN_ERR_INVALID_ARG;
+    if (!aligned(Q_win, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
+    if (p->N > 0 && (!aligned(K_hist, 16) || !aligned(V_hist, 16))) return TLIN_ERR_INVALID_ARG;
+    return TLIN_OK;
+}
+
+// The launches of a layer call; arguments and workspace have been checked.
+tlin_status layer_attn(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
+                       const void *K_win, const void *V_win, void *O, void *ws, hipStream_t hs)
+{
+    if (p->N == 0) {
+        // Empty history: the layer is the window causal attention in both combine modes.
+        AttnArgs a = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
+        set_direct(a, p, O, nullptr);
+        return launch_attn(p, true, a, hs);
+    }
+    const Plan pl = plan_history(p);
+    const int nparts = pl.nsplit + 1;
+    const Workspace w = carve(ws, p, nparts);
+
+    AttnArgs ah = base_args(p, Q_win, K_hist, V_hist, p->kh_stride, p->vh_stride, p->N);
+    ah.nsplit = pl.nsplit;
+    ah.tiles_per_split = pl.tiles_per_split;
+    set_partial(ah, w, nparts, 0);
+    AttnArgs aw = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
+    set_partial(aw, w, nparts, pl.nsplit);
+    tlin_status st;
+    if ((st = launch_partials(p, ah, aw, hs))) return st;
+    return launch_merge(p, merge_args(p, w, nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr), hs);
+}
+
 }  // namespace
 
 extern "C" {
@@ -529,10 +579,12 @@ tlin_status tlin_history_attn(const tlin_params *p, const void *Q_win, const voi
     a.nsplit = pl.nsplit;
     a.tiles_per_split = pl.tiles_per_split;
     if (pl.nsplit == 1) {
+        if ((st = check_device())) return st;
         set_direct(a, p, O, lse);
         return launch_attn(p, false, a, hs);
     }
     if ((st = check_ws(ws, ws_bytes, ws_bytes_for(p, pl.nsplit)))) return st;
+    if ((st = check_device())) return st;
     const Workspace w = carve(ws, p, pl.nsplit);
     set_partial(a, w, pl.nsplit, 0);
     if ((st = launch_attn(p, false, a, hs))) return st;
@@ -550,6 +602,7 @@ tlin_status tlin_window_causal_attn(const tlin_params *p, const void *Q_win, con
     if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
     if (!aligned(Q_win, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
     if (lse && !aligned(lse, 4)) return TLIN_ERR_INVALID_ARG;
+    if ((st = check_device())) return st;
     AttnArgs a = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
     set_direct(a, p, O, lse);
     return launch_attn(p, true, a, (hipStream_t)stream);
@@ -558,35 +611,11 @@ tlin_status tlin_window_causal_attn(const tlin_params *p, const void *Q_win, con
 tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
                             const void *K_win, const void *V_win, void *O, void *ws, size_t ws_bytes, void *stream)
 {
-    tlin_status st = check_common(p, true, true);
+    tlin_status st = check_layer_args(p, Q_win, K_hist, V_hist, K_win, V_win, O);
     if (st) return st;
-    if ((st = check_dense_rows(p, T_Q | T_KW | T_VW | T_O | (p->N > 0 ? T_KH | T_VH : 0)))) return st;
-    if (p->combine != TLIN_COMBINE_SUM && p->combine != TLIN_COMBINE_JOINT) return TLIN_ERR_INVALID_ARG;
-    if (!Q_win || !K_win || !V_win || !O) return TLIN_ERR_INVALID_ARG;
-    if (p->N > 0 && (!K_hist || !V_hist)) return TLIN_ERR_INVALID_ARG;
-    if (!aligned(Q_win, 16) || !aligned(K_win, 16) || !aligned(V_win, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
-    if (p->N > 0 && (!aligned(K_hist, 16) || !aligned(V_hist, 16))) return TLIN_ERR_INVALID_ARG;
-    hipStream_t hs = (hipStream_t)stream;
-    if (p->N == 0) {
-        // Empty history: the layer is the window causal attention in both combine modes.
-        AttnArgs a = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
-        set_direct(a, p, O, nullptr);
-        return launch_attn(p, true, a, hs);
-    }
-    const Plan pl = plan_history(p);
-    const int nparts = pl.nsplit + 1;
-    if ((st = check_ws(ws, ws_bytes, ws_bytes_for(p, nparts)))) return st;
-    const Workspace w = carve(ws, p, nparts);
-
-    AttnArgs ah = base_args(p, Q_win, K_hist, V_hist, p->kh_stride, p->vh_stride, p->N);
-    ah.nsplit = pl.nsplit;
-    ah.tiles_per_split = pl.tiles_per_split;
-    set_partial(ah, w, nparts, 0);
-    AttnArgs aw = base_args(p, Q_win, K_win, V_win, p->kw_stride, p->vw_stride, p->W);
-    set_partial(aw, w, nparts, pl.nsplit);
-    if ((st = launch_partials(p, ah, aw, hs))) return st;
-
-    return launch_merge(p, merge_args(p, w, nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr), hs);
+    if (p->N > 0 && (st = check_ws(ws, ws_bytes, ws_bytes_for(p, plan_history(p).nsplit + 1)))) return st;
+    if ((st = check_device())) return st;
+    return layer_attn(p, Q_win, K_hist, V_hist, K_win, V_win, O, ws, (hipStream_t)stream);
 }
 
 size_t tlin_slide_workspace_bytes(const tlin_params *p)
@@ -612,6 +641,7 @@ tlin_status tlin_slide_layer_attn(const tlin_params *p, const void *Q, const voi
     const SlidePlan pl = plan_slide(p);
     if ((int64_t)p->B * p->H * pl.nchunks * pl.nparts > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     if ((st = check_ws(ws, ws_bytes, slide_ws_bytes(p, pl)))) return st;
+    if ((st = check_device())) return st;
     // partial slots: (b*H + h, chunk, part), W rows each
     const size_t rows = (size_t)p->B * p->H * pl.nchunks * pl.nparts * p->W;
     float *base = (float *)ws;

@@ -8,8 +8,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def pytest_addoption(parser):
+    parser.addoption("--oracle-lib", default=None,
+                     help="run the CPU pin tests against another build of oracle/tlin_oracle.c (mutation test only)")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    lib = config.getoption("--oracle-lib")
+    if lib:
+        # a substitute oracle must never judge the GPU path
+        markexpr = config.getoption("-m") or ""
+        if "gpu" in markexpr and "not gpu" not in markexpr:
+            raise pytest.UsageError("--oracle-lib is for the CPU pin tests and is refused when GPU tests are selected")
+        import oracle
+        oracle.use_library(lib)
 
 
 @pytest.fixture(scope="session", autouse=True)

@@ -36,13 +36,22 @@ def rel_err_f32(g: np.ndarray, r: np.ndarray) -> float:
     return float(np.max(np.abs(g - r) / np.maximum(np.abs(r), rms)))
 
 
-def assert_close(g, r, dtype: int, what: str = "", lse: bool = False):
+def f32_rel_bound(max_logit_nats: float) -> float:
+    """Accuracy envelope of the fp32 path.  A logit is a 128-term fp32 sum and carries an
+    absolute rounding error of a few 2^-24 of its own size (measured: up to 3 units of
+    2^-24 * sum|q_i k_i|), which the exponential turns into the same amount of RELATIVE error in
+    the weight.  Up to 10 nats of logit magnitude that stays inside 1e-5; beyond, the bound
+    grows with the magnitude: 1e-6 per nat."""
+    return F32_REL * max(1.0, max_logit_nats / 10.0)
+
+
+def assert_close(g, r, dtype: int, what: str = "", lse: bool = False, f32_rel: float = F32_REL):
     g = to_host64(g) if isinstance(g, torch.Tensor) else np.asarray(g, dtype=np.float64)
     assert g.shape == r.shape, (g.shape, r.shape)
     assert np.isfinite(g).all(), f"{what}: non-finite output"
     if dtype == ti.F32:
         e = rel_err_f32(g, r)
-        assert e <= F32_REL, f"{what}: fp32 relative error {e:.3e} > {F32_REL}"
+        assert e <= f32_rel, f"{what}: fp32 relative error {e:.3e} > {f32_rel}"
     else:
         d = np.abs(g - r)
         assert d.max() <= BF16_MAX_ABS, f"{what}: bf16 max abs error {d.max():.3e} > {BF16_MAX_ABS}"
@@ -57,4 +66,15 @@ def sample_rows(W: int, k: int, seed: int = 0) -> np.ndarray:
     rows = {0, W - 1}
     while len(rows) < min(k, W):
         rows.add(int(rng.integers(0, W)))
+    return np.array(sorted(rows), dtype=np.int32)
+
+
+def stratified_rows(W: int, block: int = 32) -> np.ndarray:
+    """First and last row of every `block`-row group of the window.  A wave of the matrix-core
+    kernels owns 32 consecutive query rows, so this looks at every wave of every query block of
+    the launch (W = 512: 32 rows)."""
+    rows = set()
+    for r0 in range(0, W, block):
+        rows.add(r0)
+        rows.add(min(r0 + block, W) - 1)
     return np.array(sorted(rows), dtype=np.int32)

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include "tlinattn.h"
+#include "tlinattn_profile.h"
 
 static int fails = 0;
 #define CHECK(c) do { if (!(c)) { printf("FAILED line %d: %s\n", __LINE__, #c); ++fails; } } while (0)

@@ -14,9 +14,14 @@ pytestmark = pytest.mark.skipif(not os.path.exists(b.LIB_PATH), reason="libtlina
 
 
 def header_symbols():
-    text = open(os.path.join(ROOT, "include", "tlinattn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tlin_[a-z_]+)\s*\(", text)))
+    syms = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not name.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        syms |= set(re.findall(r"\b(tlin_[a-z_]+)\s*\(", text))
+    return sorted(syms)
 
 
 def test_library_exports_every_declared_symbol():

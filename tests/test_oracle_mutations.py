@@ -47,9 +47,10 @@ def build_and_run_pins(tmp, tag, source):
     with open(c, "w") as f:
         f.write(source)
     subprocess.run(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", so, c, "-lm"], check=True)
-    env = dict(os.environ, TLIN_ORACLE_LIB=so, OMP_NUM_THREADS="2")
+    env = dict(os.environ, OMP_NUM_THREADS="2")
     r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
-                        "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+                        "-m", "not gpu", "--oracle-lib", so, "-p", "no:cacheprovider"], cwd=ROOT, env=env,
+                       capture_output=True, text=True, timeout=600)
     return r.returncode, r.stdout[-1500:]
 
 
@@ -62,5 +63,9 @@ def test_pins_pass_on_the_real_oracle_and_fail_on_every_planted_mistake(tmp_path
     assert rc == 0, "pins fail on the unmodified oracle built through the hook:\n" + out
     survived = [MUTATIONS[i][0] for i, (rc, _) in enumerate(results[1:]) if rc == 0]
     assert not survived, f"planted mistakes that no pin noticed: {survived}"
+    # the substitute-oracle option must be refused as soon as GPU tests are selected
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests"), "-q", "-m", "gpu", "--collect-only",
+                        "--oracle-lib", SRC, "-p", "no:cacheprovider"], cwd=ROOT, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 4 and "refused" in (r.stdout + r.stderr), (r.returncode, r.stderr[-500:])
     for (name, *_), (rc, out) in zip(MUTATIONS, results[1:]):
         assert rc == 1, f"{name}: pytest ended with {rc} (expected test failures, not a crash):\n{out}"

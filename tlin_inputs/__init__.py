@@ -139,6 +139,9 @@ def degenerate_causal() -> Workload:
 
 
 def shrink(w: Workload, **kw) -> Workload:
+    """The workload with some fields changed; unless a name is given, the new one says which."""
+    if kw and "name" not in kw:
+        kw["name"] = w.name + "_changed_" + "_".join(f"{k}{v}" for k, v in sorted(kw.items()))
     return replace(w, **kw)
 
 
