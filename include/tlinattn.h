@@ -130,6 +130,22 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
                             const void *V_hist, const void *K_win, const void *V_win, void *O,
                             void *ws, size_t ws_bytes, void *stream);
 
+/* tlin_layer_attn for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels, with the split partials kept in a device array that is part of the library's code
+ * object (TLIN_STATIC_WS_BYTES per GPU, held from the library's load to the end of the process).
+ * The call allocates nothing; the array's address is looked up once per device, on the first call
+ * made with that device current.  Parameters whose tlin_workspace_bytes(p) exceeds
+ * TLIN_STATIC_WS_BYTES are rejected with TLIN_ERR_WORKSPACE before anything is launched
+ * (p->num_splits can lower the need).  Every partial that is read has been written by the same
+ * call, so nothing in the array needs clearing between calls; it keeps the previous call's
+ * contents.  All calls on one GPU share the array: calls that overlap on one GPU (different
+ * streams, or threads) race; order them on one stream. */
+#define TLIN_STATIC_WS_BYTES ((size_t)64 << 20)
+tlin_status tlin_layer_attn_static_ws(const tlin_params *p, const void *Q_win, const void *K_hist,
+                                      const void *V_hist, const void *K_win, const void *V_win,
+                                      void *O, void *stream);
+
 /* The sliding schedule of Section 5.1 over a whole sequence in one call: the sequence of
  * p->N rows is cut into chunks of p->W rows (the last one may be shorter); chunk c is a window
  * whose history is every earlier chunk, so row c*W + i attends rows [0, c*W) of K_hist/V_hist

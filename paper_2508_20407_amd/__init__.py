@@ -10,7 +10,7 @@ from __future__ import annotations
 from . import binding
 from .binding import (TLIN_BF16, TLIN_COMBINE_JOINT, TLIN_COMBINE_SUM, TLIN_F32, TlinError, TlinParams)
 
-__all__ = ["tlin_history_attn", "tlin_window_causal_attn", "tlin_layer_attn", "tlin_slide_layer_attn", "Workspace", "params_for",
+__all__ = ["tlin_history_attn", "tlin_window_causal_attn", "tlin_layer_attn", "tlin_layer_attn_static_ws", "tlin_slide_layer_attn", "Workspace", "params_for",
            "TLIN_F32", "TLIN_BF16", "TLIN_COMBINE_SUM", "TLIN_COMBINE_JOINT", "TlinError", "TlinParams",
            "binding"]
 
@@ -143,6 +143,24 @@ def tlin_layer_attn(q_win, k_hist, v_hist, k_win, v_win, *, combine=TLIN_COMBINE
                                 v_hist.data_ptr() if n else None, k_win.data_ptr(), v_win.data_ptr(),
                                 o.data_ptr(), ws or None, nb, _stream(q_win))
     binding._check(st, "tlin_layer_attn")
+    return o
+
+
+def tlin_layer_attn_static_ws(q_win, k_hist, v_hist, k_win, v_win, *, combine=TLIN_COMBINE_SUM, scale=None, out=None,
+                              num_splits=0):
+    """tlin_layer_attn with the library's own static device array as workspace.  With `out` (a
+    [B,H,W,D] tensor of the wanted output type) the call allocates nothing at all."""
+    _require_gpu(q_win, k_hist, v_hist, k_win, v_win, out)
+    n = 0 if k_hist is None else k_hist.shape[2]
+    o = _out(q_win, None) if out is None else out
+    if tuple(o.shape) != tuple(q_win.shape):
+        raise ValueError("out must have the shape of q_win")
+    p = params_for(q_win, n, o.dtype, scale, num_splits, combine,
+                   kh=k_hist if n else None, vh=v_hist if n else None, kw=k_win, vw=v_win, o=o)
+    st = binding.layer_attn_static_ws_raw(p, q_win.data_ptr(), k_hist.data_ptr() if n else None,
+                                          v_hist.data_ptr() if n else None, k_win.data_ptr(), v_win.data_ptr(),
+                                          o.data_ptr(), _stream(q_win))
+    binding._check(st, "tlin_layer_attn_static_ws")
     return o
 
 

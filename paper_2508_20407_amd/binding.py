@@ -17,7 +17,7 @@ TLIN_F32, TLIN_BF16 = 0, 1
 TLIN_COMBINE_SUM, TLIN_COMBINE_JOINT = 0, 1
 
 EXPORTS = ("tlin_workspace_bytes", "tlin_num_splits", "tlin_history_attn", "tlin_window_causal_attn",
-           "tlin_layer_attn", "tlin_slide_workspace_bytes", "tlin_slide_layer_attn", "tlin_profile_enable", "tlin_profile_read", "tlin_status_string", "tlin_version")
+           "tlin_layer_attn", "tlin_layer_attn_static_ws", "tlin_slide_workspace_bytes", "tlin_slide_layer_attn", "tlin_profile_enable", "tlin_profile_read", "tlin_status_string", "tlin_version")
 
 
 class TlinParams(ctypes.Structure):
@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.tlin_window_causal_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tlin_layer_attn.restype = ctypes.c_int
         L.tlin_layer_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tlin_layer_attn_static_ws.restype = ctypes.c_int
+        L.tlin_layer_attn_static_ws.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
         L.tlin_slide_workspace_bytes.restype = sz
         L.tlin_slide_workspace_bytes.argtypes = [pp]
         L.tlin_slide_layer_attn.restype = ctypes.c_int
@@ -121,6 +123,13 @@ def window_causal_attn_raw(p, q, kw, vw, o, lse, ws, ws_bytes, stream) -> int:
 
 def layer_attn_raw(p, q, kh, vh, kw, vw, o, ws, ws_bytes, stream) -> int:
     return int(lib().tlin_layer_attn(ctypes.byref(p), q, kh, vh, kw, vw, o, ws, ws_bytes, stream))
+
+
+STATIC_WS_BYTES = 64 << 20   # TLIN_STATIC_WS_BYTES
+
+
+def layer_attn_static_ws_raw(p, q, kh, vh, kw, vw, o, stream) -> int:
+    return int(lib().tlin_layer_attn_static_ws(ctypes.byref(p), q, kh, vh, kw, vw, o, stream))
 
 
 def slide_workspace_bytes(p: TlinParams) -> int:

@@ -17,6 +17,11 @@
 
 using namespace tlin;
 
+// Workspace of tlin_layer_attn_static_ws: split partials of the history axis and the window
+// partial, for callers that cannot bring device memory of their own.  Host code never uses this
+// name as an address; static_scratch() asks the runtime for the array's address on the current device.
+static __device__ __align__(256) unsigned char scratch[TLIN_STATIC_WS_BYTES];
+
 namespace {
 
 constexpr int kVersion = 200;   // 0.2.0
@@ -547,6 +552,24 @@ tlin_status layer_attn(const tlin_params *p, const void *Q_win, const void *K_hi
     return launch_merge(p, merge_args(p, w, nparts, pl.nsplit, true, p->combine == TLIN_COMBINE_JOINT, O, nullptr), hs);
 }
 
+// Address of this device's copy of `scratch`, looked up once per device ordinal with that device
+// current (every GPU holds its own copy of the array at its own address).
+tlin_status static_scratch(void **out)
+{
+    static std::mutex mu;
+    static void *addr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TLIN_ERR_HIP;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!addr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TLIN_ERR_HIP;
+        addr[dev] = ptr;
+    }
+    *out = addr[dev];
+    return TLIN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -615,6 +638,19 @@ tlin_status tlin_layer_attn(const tlin_params *p, const void *Q_win, const void 
     if (st) return st;
     if (p->N > 0 && (st = check_ws(ws, ws_bytes, ws_bytes_for(p, plan_history(p).nsplit + 1)))) return st;
     if ((st = check_device())) return st;
+    return layer_attn(p, Q_win, K_hist, V_hist, K_win, V_win, O, ws, (hipStream_t)stream);
+}
+
+tlin_status tlin_layer_attn_static_ws(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
+                                      const void *K_win, const void *V_win, void *O, void *stream)
+{
+    tlin_status st = check_layer_args(p, Q_win, K_hist, V_hist, K_win, V_win, O);
+    if (st) return st;
+    const size_t need = p->N > 0 ? ws_bytes_for(p, plan_history(p).nsplit + 1) : 0;
+    if (need > TLIN_STATIC_WS_BYTES) return TLIN_ERR_WORKSPACE;
+    if ((st = check_device())) return st;
+    void *ws = nullptr;
+    if (need > 0 && (st = static_scratch(&ws))) return st;
     return layer_attn(p, Q_win, K_hist, V_hist, K_win, V_win, O, ws, (hipStream_t)stream);
 }
 

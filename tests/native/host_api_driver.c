@@ -63,6 +63,16 @@ int main(void)
     CHECK(tlin_slide_layer_attn(&p, fake, fake, fake, fake, fake, fake, fake, 1u << 30, NULL) == TLIN_ERR_INVALID_ARG);
     p.N = 1024; p.q_stride[0] = 1; p.q_stride[1] = 8; p.q_stride[2] = 24;   /* row stride < D */
     CHECK(tlin_history_attn(&p, fake, fake, fake, fake, NULL, fake, 1u << 30, NULL) == TLIN_ERR_INVALID_ARG);
+    /* the static-workspace layer call: same argument checks, and its size limit, all on the host */
+    tlin_params sp = params(1, 32, 512, 131072, 128, TLIN_BF16);
+    CHECK(tlin_workspace_bytes(&sp) <= TLIN_STATIC_WS_BYTES);
+    CHECK(tlin_layer_attn_static_ws(&sp, NULL, fake, fake, fake, fake, fake, NULL) == TLIN_ERR_INVALID_ARG);
+    CHECK(tlin_layer_attn_static_ws(&sp, fake, fake, fake, fake, (char *)fake + 8, fake, NULL) == TLIN_ERR_INVALID_ARG);
+    sp.B = 4;
+    CHECK(tlin_workspace_bytes(&sp) > TLIN_STATIC_WS_BYTES);
+    CHECK(tlin_layer_attn_static_ws(&sp, fake, fake, fake, fake, fake, fake, NULL) == TLIN_ERR_WORKSPACE);
+    sp.combine = 9;
+    CHECK(tlin_layer_attn_static_ws(&sp, fake, fake, fake, fake, fake, fake, NULL) == TLIN_ERR_INVALID_ARG);
     double ms[3]; int64_t n[3];
     CHECK(tlin_profile_read(NULL, n) == TLIN_ERR_INVALID_ARG);
     CHECK(tlin_profile_read(ms, n) == TLIN_OK && n[0] == 0 && n[1] == 0 && n[2] == 0);

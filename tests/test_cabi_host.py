@@ -117,6 +117,21 @@ def test_null_and_misaligned_pointers_and_workspace():
     assert b.layer_attn_raw(P(N=-1), A, A, A, A, A, A, A, big, None) == b.TLIN_ERR_INVALID_ARG
 
 
+def test_static_workspace_entry_point_checks_arguments_and_its_limit_on_the_host():
+    p = P()
+    assert b.layer_attn_static_ws_raw(p, None, A, A, A, A, A, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.layer_attn_static_ws_raw(P(combine=3), A, A, A, A, A, A, None) == b.TLIN_ERR_INVALID_ARG
+    assert b.layer_attn_static_ws_raw(P(W=0), A, A, A, A, A, A, None) == b.TLIN_ERR_INVALID_ARG
+    # a workspace need beyond the array's size is refused before any device call
+    big = P(B=4, H=32, W=512, N=131072, D=128)
+    assert b.workspace_bytes(big) > b.STATIC_WS_BYTES
+    assert b.layer_attn_static_ws_raw(big, A, A, A, A, A, A, None) == b.TLIN_ERR_WORKSPACE
+    # the largest fixed workload fits
+    assert b.workspace_bytes(P(B=1, H=32, W=512, N=131072, D=128)) <= b.STATIC_WS_BYTES
+    text = open(os.path.join(ROOT, "include", "tlinattn.h")).read()
+    assert "#define TLIN_STATIC_WS_BYTES ((size_t)64 << 20)" in text and b.STATIC_WS_BYTES == 64 << 20
+
+
 def test_slide_planning_and_argument_checks():
     # 256 chunks of 512 rows, 32 heads: plenty of work items, so one partition per chunk history
     # plus the window partial = 2 fp32 partial slots per output row
