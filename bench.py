@@ -36,6 +36,9 @@ def parse():
     # after the idle time of the input upload the chip needs some 30-50 ms of load to reach the clocks
     # it then holds: the default warm-up covers that
     ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="untimed steps run before the warm-up until this much time has passed: the chip needs some "
+                         "30-50 ms of the same load to settle at the clocks it then holds (reported as settle_steps)")
     ap.add_argument("--config", type=int, default=4, help="1..4: the fixed workloads (default 4: N=131072, W=512, bf16)")
     ap.add_argument("--combine", choices=("sum", "joint"), default="sum")
     ap.add_argument("--num-splits", type=int, default=0)
@@ -81,6 +84,22 @@ def upload(host, dtype, ti, torch, np):
             t = buf[..., :D]
         dev[k] = t
     return dev
+
+
+def settle(fn, min_ms, torch):
+    """Untimed steps until min_ms of wall time have passed (in batches, with a synchronisation after
+    each): after the idle time of the input upload the chip ramps its clocks for some tens of
+    milliseconds, which a short warm-up would leave inside the timed region.  Returns the number
+    of steps run."""
+    n = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while min_ms > 0 and (time.perf_counter() - t0) * 1e3 < min_ms:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        n += 10
+    return n
 
 
 def time_steps(fn, steps, warmup, torch):
@@ -138,15 +157,16 @@ def gemm_context(torch, n=8192, iters=50):
         return {"library_bf16_gemm_TFLOPs": None, "error": repr(e)}
 
 
-def cpu_baseline(w, host, target_s, oracle, np, layer=True):
-    """Oracle on a seeded row sample sized for about target_s seconds; returns the JSON object.
-    layer=True: the layer call (SUM: one history softmax plus one window softmax per row);
-    layer=False: history attention only."""
+def cpu_baseline(w, host, target_s, oracle, np, layer=True, joint=False):
+    """Oracle on a seeded row sample sized for about target_s seconds; returns the JSON object, the
+    sampled rows and the oracle's output for them (which the caller compares with the GPU's).
+    layer=True: the layer call (one history softmax plus one window softmax per row, or one joint
+    softmax); layer=False: history attention only."""
     def run(rows):
         if layer:
-            oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, oracle.SUM, rows)
-        else:
-            oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)
+            return oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale,
+                                oracle.JOINT if joint else oracle.SUM, rows)
+        return oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)[0]
     rng = np.random.default_rng(12345)
     probe = np.sort(rng.choice(w.W, size=min(w.W, 1), replace=False)).astype(np.int32)
     t0 = time.perf_counter()
@@ -155,10 +175,10 @@ def cpu_baseline(w, host, target_s, oracle, np, layer=True):
     rows_per_head = int(max(1, min(w.W, target_s / max(t_probe, 1e-4) * len(probe))))
     rows = np.sort(rng.choice(w.W, size=rows_per_head, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    run(rows)
+    ref = run(rows)
     dt = time.perf_counter() - t0
     flops = 4.0 * w.B * w.H * w.D * (len(rows) * w.N + (float(np.sum(rows + 1)) if layer else 0.0))
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+    return rows, ref, {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"{len(rows)} of {w.W} window rows in each of {w.B * w.H} heads, full history, fp64, "
                       f"{dt:.1f} s",
             "window_tokens_per_s": w.B * len(rows) / dt * (1.0),
@@ -238,6 +258,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    settle_steps = settle(step, args.settle_ms, torch)
     sec = time_steps(step, args.steps, args.warmup, torch)
 
     # Spread of single steps: the same K steps again, each between its own pair of events on the
@@ -310,16 +331,19 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": hist_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # both fractions, whichever binds (shapes near the ridge sit between the two roofs)
+    roof["frac_mfma"] = hist_tflops / peak_mfma
+    roof["frac_hbm"] = hist_gbs / PEAK_HBM_GBS
     kname = "attn_f32" if w.dtype == ti.F32 else "attn_bf16"
     roof["kernel"] = (f"{kname}_pair_kernel (history partitions + window blocks)" if paired else
                       f"{kname}_kernel (history partitions)")
     roof["kernel_ms"] = hist_ms
-    roof["traffic"] = measured_traffic(w.name)
+    roof["traffic"], roof["traffic_source"] = measured_traffic(w.name)
 
     out = {
         "metric": metric,
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": sec * 1e3, "ms_per_step_median": step_median, "ms_per_step_min": step_min,
+        "settle_steps": settle_steps, "ms_per_step": sec * 1e3, "ms_per_step_median": step_median, "ms_per_step_min": step_min,
         "ms_per_step_hip_graph": graph_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == ti.F32 else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "D": w.D, "N_history": w.N, "W_window": w.W,
@@ -337,22 +361,57 @@ def main():
             out["context"]["kernel_vs_library_gemm"] = hist_tflops / out["context"]["library_bf16_gemm_TFLOPs"]
     if not args.no_cpu_baseline:
         import oracle
-        out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np, layer)
+        rows, ref, out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np, layer, args.combine == "joint")
+        # the output of the timed call against the oracle rows just computed (every K/V copy that
+        # the steps rotate through holds the same values)
+        got = step()[:, :, torch.from_numpy(rows).long().cuda()].float().cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref)
+        out["parity"] = {"rows": int(len(rows) * w.B * w.H), "rows_per_head": int(len(rows)), "max_abs": float(err.max()),
+                         "mean_abs": float(err.mean()), "against": "the oracle rows of cpu_baseline"}
+        if w.dtype == ti.F32:
+            rms = float(np.sqrt(np.mean(ref * ref)))
+            out["parity"]["max_rel"] = float(np.max(err / np.maximum(np.abs(ref), rms)))
+            out["parity"]["ok"] = out["parity"]["max_rel"] <= 1e-5
+        else:
+            out["parity"]["ok"] = bool(err.max() <= 2e-2 and err.mean() <= 5e-3)
     print(json.dumps(out), flush=True)
+    if "parity" in out and not out["parity"]["ok"]:
+        print("bench.py: the timed call's output is outside the tolerance against the oracle", file=sys.stderr)
+        sys.exit(1)
 
 
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (two runs of this script with --calibrate-copy; raw readings, commands and the scale factors of the
-# two counters are in profiles/attn_bf16_pair_cfg4_pmc.md and profiles/attn_bf16_history_decode_w1.md).
-# None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg4_bf16_N131072_W512": int(1_056_884.3 * 2.0 * 1024) + 41_600 * 1024,   # 2.016 GiB fetched + 40.6 MiB written
-    "decode_bf16_N131072_W1": int(1_048_648.7 * 2.0 * 1024) + 260 * 1024,      # 2.0001 GiB fetched + 260 KiB written
+# two counters are in the profile files named here).  A figure is only reported while the kernel
+# sources are the ones it was measured on (csrc_sha16 below = kernel_sources_sha16() at that time);
+# otherwise `traffic` is null and `traffic_source` says why.
+MEASURED_TRAFFIC = {
+    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_884.3 * 2.0 * 1024) + 41_600 * 1024,   # 2.016 GiB fetched + 40.6 MiB written
+                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "unset"},
+    "decode_bf16_N131072_W1": {"bytes": int(1_048_648.7 * 2.0 * 1024) + 260 * 1024,      # 2.0001 GiB fetched + 260 KiB written
+                               "profile": "profiles/attn_bf16_history_decode_w1.md", "csrc_sha16": "unset"},
 }
 
 
+def kernel_sources_sha16():
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2508_20407_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(name):
-    return MEASURED_TRAFFIC_BYTES.get(name)
+    m = MEASURED_TRAFFIC.get(name)
+    now = kernel_sources_sha16()
+    if m is None:
+        return None, {"note": "not measured for this workload", "csrc_sha16": now}
+    if m["csrc_sha16"] != now:
+        return None, {"note": "kernel sources changed since the counter run in " + m["profile"], "csrc_sha16": now,
+                      "measured_at_csrc_sha16": m["csrc_sha16"]}
+    return m["bytes"], {"profile": m["profile"], "csrc_sha16": now}
 
 
 def slide(args, ti, tl, binding, torch, np, combine):
@@ -370,6 +429,7 @@ def slide(args, ti, tl, binding, torch, np, combine):
         return tl.tlin_slide_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], W, combine=combine,
                                         scale=w.scale, num_splits=args.num_splits, workspace=ws)
 
+    settle_steps = settle(step, args.settle_ms, torch)
     sec = time_steps(step, args.steps, args.warmup, torch)
     binding.profile_enable(True)
     for _ in range(args.steps):
@@ -394,7 +454,7 @@ def slide(args, ti, tl, binding, torch, np, combine):
         roof.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS})
     out = {"metric": "sliding schedule over a whole sequence (Section 5.1), bf16: TFLOP/s and tokens/s",
            "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "settle_steps": settle_steps, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": w.name, "B": w.B, "H": w.H, "D": w.D, "L_sequence": L, "W_chunk": W,
                       "combine": args.combine, "step": "tlin_slide_layer_attn = chunk histories + chunk causal + merge"},
@@ -405,13 +465,19 @@ def slide(args, ti, tl, binding, torch, np, combine):
         rng = np.random.default_rng(12345)
         probe = np.sort(rng.choice(L, size=2, replace=False)).astype(np.int32)
         t0 = time.perf_counter()
-        oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, W, oracle.SUM, probe)
+        oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, W,
+                     oracle.JOINT if args.combine == "joint" else oracle.SUM, probe)
         t_probe = time.perf_counter() - t0
         n = int(max(2, min(L, args.cpu_seconds / max(t_probe, 1e-4) * len(probe))))
         rows = np.sort(rng.choice(L, size=n, replace=False)).astype(np.int32)
         t0 = time.perf_counter()
-        oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, W, oracle.SUM, rows)
+        ref = oracle.slide(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, W,
+                           oracle.JOINT if args.combine == "joint" else oracle.SUM, rows)
         dt = time.perf_counter() - t0
+        got = step()[:, :, torch.from_numpy(rows).long().cuda()].float().cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref)
+        out["parity"] = {"rows": int(n * bh), "rows_per_head": int(n), "max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                         "ok": bool(err.max() <= 2e-2 and err.mean() <= 5e-3), "against": "the oracle rows of cpu_baseline"}
         keys = float(np.sum(rows + 1))                # history rows + visible window rows of each sampled position
         out["cpu_baseline"] = {"value": 4.0 * bh * w.D * keys / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
                                "kind": "oracle", "sample": f"{n} of {L} sequence positions in each of {bh} heads, fp64, "
