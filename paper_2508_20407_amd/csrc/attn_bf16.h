@@ -487,21 +487,24 @@ constexpr bool use_pipe_body()
     return !CAUSAL && !RESIDENT && QB == 1 && NSTAGE == 2;
 }
 
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false, bool PAD = false>
+// NT (pipelined shapes only): the tile loads carry the non-temporal hint, see direct_load_1k.
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false, bool PAD = false, bool NT = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
 void attn_bf16_kernel(const AttnArgs a)
 {
-    if constexpr (use_pipe_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>()) attn_bf16_pipe_body<D, NW, PAD>(a, blockIdx.x, gridDim.x);
+    static_assert(!NT || use_pipe_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>(), "only the pipelined body has a non-temporal variant");
+    if constexpr (use_pipe_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>()) attn_bf16_pipe_body<D, NW, PAD, NT>(a, blockIdx.x, gridDim.x);
     else attn_bf16_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>(a, blockIdx.x, gridDim.x);
 }
 
 // History partition blocks and window causal blocks of one call in a single launch.
-template <int D, int NW, int NSTAGE, bool PAD = false>
+template <int D, int NW, int NSTAGE, bool PAD = false, bool NT = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))
 void attn_bf16_pair_kernel(const PairArgs f)
 {
+    static_assert(!NT || use_pipe_body<D, NW, 1, false, NSTAGE, false>(), "only the pipelined body has a non-temporal variant");
     if ((int)blockIdx.x < f.n_hist_blocks) {
-        if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) attn_bf16_pipe_body<D, NW, PAD>(f.hist, blockIdx.x, f.n_hist_blocks);
+        if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) attn_bf16_pipe_body<D, NW, PAD, NT>(f.hist, blockIdx.x, f.n_hist_blocks);
         else attn_bf16_body<D, NW, 1, false, NSTAGE, false, PAD>(f.hist, blockIdx.x, f.n_hist_blocks);
     } else {
         attn_bf16_body<D, NW, 1, true, NSTAGE, false, PAD>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);

@@ -46,7 +46,7 @@ __device__ __forceinline__ void static_for_seq(F &&f, std::integer_sequence<int,
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F &&f) { static_for_seq(f, std::make_integer_sequence<int, N>{}); }
 
-template <int D, int NW, bool PAD>
+template <int D, int NW, bool PAD, bool NT>
 __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, int nblocks)
 {
     constexpr int NSTAGE = 2;
@@ -130,14 +130,14 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
         const int rows = min(BN, NK - key0);
         const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
 #pragma unroll
-        for (int i = 0; i < NDMA; ++i) direct_load_1k(kd, koff[i], lds_wave + stage * TILE_B + i * 1024);
+        for (int i = 0; i < NDMA; ++i) direct_load_1k<NT>(kd, koff[i], lds_wave + stage * TILE_B + i * 1024);
     };
     auto issue_v = [&](int n, int stage) __attribute__((always_inline)) {
         const int key0 = (t0 + n) * BN;
         const int rows = min(BN, NK - key0);
         const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
 #pragma unroll
-        for (int i = 0; i < NDMA; ++i) direct_load_1k(vd, voff[i], lds_wave + (NSTAGE + stage) * TILE_B + i * 1024);
+        for (int i = 0; i < NDMA; ++i) direct_load_1k<NT>(vd, voff[i], lds_wave + (NSTAGE + stage) * TILE_B + i * 1024);
     };
     auto scrub = [&](int stage) __attribute__((always_inline)) {
         if (!PAD || !(a.D & 7)) return;
@@ -263,7 +263,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
         const int64_t rb = isk ? k_rb : v_rb;
         const u32x4 d = tile_descriptor((isk ? Kg : Vg) + key0 * rb, rows < BN ? (unsigned)(rows * rb) : 0xffffffffu);
         const int ii = isk ? i : i - NDMA;
-        direct_load_1k(d, isk ? koff[ii] : voff[ii], lds_wave + ((isk ? kfree : NSTAGE + vfree)) * TILE_B + ii * 1024);
+        direct_load_1k<NT>(d, isk ? koff[ii] : voff[ii], lds_wave + ((isk ? kfree : NSTAGE + vfree)) * TILE_B + ii * 1024);
     };
     // Schedule parameters (measured on the largest fixed workload; neighbouring values are within 1 %).
     constexpr int PIPE_KPF = 4;       // K fragments requested ahead of their product

@@ -13,6 +13,7 @@
 
 #include "attn_bf16.h"
 #include "attn_f32.h"
+#include "decode_bf16.h"
 #include "merge.h"
 
 using namespace tlin;
@@ -226,6 +227,34 @@ Plan plan_history(const tlin_params *p)
     return {(ntiles + tps - 1) / tps, tps};   // no partition is empty
 }
 
+// The cache-hit shape (a few query rows, long bf16 history, head dimension 128) runs in the
+// streaming kernel of decode_bf16.h when called through tlin_history_attn.
+bool use_decode(const tlin_params *p)
+{
+    return p->in_dtype == TLIN_BF16 && p->D == 128 && p->W <= 4 && p->N >= 1024;
+}
+
+// One workgroup per partition; four per compute unit (they are small: four waves; more partitions
+// only lengthen the merge), at least 256 rows each.
+Plan plan_decode(const tlin_params *p)
+{
+    const int ntiles = (p->N + 63) / 64;
+    int want;
+    if (p->num_splits > 0) {
+        want = p->num_splits;
+    } else {
+        const int64_t bh = (int64_t)p->B * p->H;
+        want = (int)((4 * (int64_t)kNumCU + bh - 1) / bh);
+        const int cap = ntiles / 4 > 1 ? ntiles / 4 : 1;
+        if (want > cap) want = cap;
+    }
+    if (want < 1) want = 1;
+    if (want > ntiles) want = ntiles;
+    if (want > 1024) want = 1024;
+    const int tps = (ntiles + want - 1) / want;
+    return {(ntiles + tps - 1) / tps, tps};
+}
+
 // Sliding schedule: chunks of W rows over a sequence of N rows; every chunk's history is cut into
 // the same number of partitions (their length grows with the chunk index).
 struct SlidePlan { int nchunks, nsplit, nparts; };
@@ -291,15 +320,25 @@ tlin_status allow_lds(const void *kernel, int lds_bytes, std::atomic<uint64_t> &
     return TLIN_OK;
 }
 
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT, bool PAD>
-tlin_status launch_bf16_shape_pad(const AttnArgs &a, int grid, hipStream_t st)
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT, bool PAD, bool NT>
+tlin_status launch_bf16_kernel(const AttnArgs &a, int grid, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>;
+    auto kernel = attn_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD, NT>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
     return launch_kernel((const void *)kernel, dim3(grid), dim3(NW * 64), lds_bytes, st, a);
+}
+
+// The non-temporal variant exists for the pipelined shapes only.
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT, bool PAD>
+tlin_status launch_bf16_shape_pad(const AttnArgs &a, int grid, hipStream_t st)
+{
+    if constexpr (use_pipe_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT>()) {
+        if (a.stream_once) return launch_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD, true>(a, grid, st);
+    }
+    return launch_bf16_kernel<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD, false>(a, grid, st);
 }
 
 // The variant with a.D below the kernel's D is a kernel of its own, so that the exact sizes carry
@@ -358,11 +397,22 @@ bool use_resident(const tlin_params *p, bool causal, const AttnArgs &a)
     return ntiles <= resident_tiles(dpad(p->D)) && blocks >= 4 * (int64_t)kNumCU;
 }
 
+// K/V rows of a history are read by exactly one workgroup when the window is a single query block,
+// and stream through the caches without reuse when they exceed the last-level cache (256 MB)
+// several times over: then the tile loads carry the non-temporal hint.  Not for the sliding
+// schedule, whose chunks re-read each other's history.
+bool streams_once(const tlin_params *p, const AttnArgs &a, int nqb)
+{
+    const int64_t kv_bytes = 2 * (int64_t)p->B * p->H * a.NK * p->D * 2;
+    return p->in_dtype == TLIN_BF16 && nqb == 1 && a.nchunks == 0 && kv_bytes >= ((int64_t)192 << 20);
+}
+
 // Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
 tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream_t st)
 {
     const int qblk = query_block(p->in_dtype, p->W);
     a.nqb = (p->W + qblk - 1) / qblk;
+    a.stream_once = !causal && streams_once(p, a, a.nqb);
     if (use_resident(p, causal, a)) {
         // one workgroup per compute unit, spread evenly over the heads
         const int64_t bh = (int64_t)p->B * p->H;
@@ -386,6 +436,16 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
     }
     if (dpad(p->D) == 128) return causal ? launch_f32<128, true>(a, s, grid, st) : launch_f32<128, false>(a, s, grid, st);
     return causal ? launch_f32<64, true>(a, s, grid, st) : launch_f32<64, false>(a, s, grid, st);
+}
+
+tlin_status launch_decode(const tlin_params *p, const AttnArgs &a, hipStream_t st)
+{
+    const int64_t grid64 = (int64_t)p->B * p->H * a.nsplit;
+    if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
+    LaunchTimer timer(KC_HISTORY, st);
+    const void *kernel = p->W == 1 ? (const void *)decode_bf16_kernel<1> : p->W == 2 ? (const void *)decode_bf16_kernel<2>
+                                                                                      : (const void *)decode_bf16_kernel<4>;
+    return launch_kernel(kernel, dim3((unsigned)grid64), dim3(256), 0, st, a);
 }
 
 tlin_status launch_merge(const tlin_params *p, MergeArgs m, hipStream_t st)
@@ -456,15 +516,24 @@ MergeArgs merge_args(const tlin_params *p, const Workspace &w, int nparts, int n
     return m;
 }
 
-template <int D, int NW, int NSTAGE, bool PAD>
-tlin_status launch_pair_shape_pad(const PairArgs &f, hipStream_t st)
+template <int D, int NW, int NSTAGE, bool PAD, bool NT>
+tlin_status launch_pair_kernel(const PairArgs &f, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * NSTAGE * 64 * D * 2;
     static_assert(lds_bytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a gfx950 compute unit");
-    auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE, PAD>;
+    auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE, PAD, NT>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
     return launch_kernel((const void *)kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
+}
+
+template <int D, int NW, int NSTAGE, bool PAD>
+tlin_status launch_pair_shape_pad(const PairArgs &f, hipStream_t st)
+{
+    if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) {
+        if (f.hist.stream_once) return launch_pair_kernel<D, NW, NSTAGE, PAD, true>(f, st);
+    }
+    return launch_pair_kernel<D, NW, NSTAGE, PAD, false>(f, st);
 }
 
 template <int D, int NW, int NSTAGE>
@@ -486,6 +555,7 @@ tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const Attn
         f.hist = ah;
         f.win = aw;
         f.hist.nqb = f.win.nqb = nqb;
+        f.hist.stream_once = streams_once(p, ah, nqb);
         f.n_hist_blocks = (int)nh;
         f.n_win_blocks = (int)nw;
         const Shape s = bf16_shape(p->W);
@@ -578,13 +648,18 @@ size_t tlin_workspace_bytes(const tlin_params *p)
 {
     if (check_common(p, true, true) != TLIN_OK) return 0;
     const Plan pl = plan_history(p);
-    return ws_bytes_for(p, pl.nsplit + 1);
+    size_t need = ws_bytes_for(p, pl.nsplit + 1);
+    if (use_decode(p)) {
+        const size_t dec = ws_bytes_for(p, plan_decode(p).nsplit);
+        if (dec > need) need = dec;
+    }
+    return need;
 }
 
 int32_t tlin_num_splits(const tlin_params *p)
 {
     if (check_common(p, true, false) != TLIN_OK) return 0;
-    return plan_history(p).nsplit;
+    return use_decode(p) ? plan_decode(p).nsplit : plan_history(p).nsplit;
 }
 
 tlin_status tlin_history_attn(const tlin_params *p, const void *Q_win, const void *K_hist, const void *V_hist,
@@ -596,9 +671,20 @@ tlin_status tlin_history_attn(const tlin_params *p, const void *Q_win, const voi
     if (!Q_win || !K_hist || !V_hist || !O) return TLIN_ERR_INVALID_ARG;
     if (!aligned(Q_win, 16) || !aligned(K_hist, 16) || !aligned(V_hist, 16) || !aligned(O, 16)) return TLIN_ERR_INVALID_ARG;
     if (lse && !aligned(lse, 4)) return TLIN_ERR_INVALID_ARG;
-    const Plan pl = plan_history(p);
     hipStream_t hs = (hipStream_t)stream;
     AttnArgs a = base_args(p, Q_win, K_hist, V_hist, p->kh_stride, p->vh_stride, p->N);
+    if (use_decode(p)) {
+        const Plan pd = plan_decode(p);
+        if ((st = check_ws(ws, ws_bytes, ws_bytes_for(p, pd.nsplit)))) return st;
+        if ((st = check_device())) return st;
+        const Workspace w = carve(ws, p, pd.nsplit);
+        a.nsplit = pd.nsplit;
+        a.tiles_per_split = pd.tiles_per_split;
+        set_partial(a, w, pd.nsplit, 0);
+        if ((st = launch_decode(p, a, hs))) return st;
+        return launch_merge(p, merge_args(p, w, pd.nsplit, pd.nsplit, false, true, O, lse), hs);
+    }
+    const Plan pl = plan_history(p);
     a.nsplit = pl.nsplit;
     a.tiles_per_split = pl.tiles_per_split;
     if (pl.nsplit == 1) {

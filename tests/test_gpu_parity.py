@@ -106,6 +106,40 @@ def test_decode_shape_full_size_every_row(W):
     run_all(ti.decode_point(131072, W))
 
 
+@pytest.mark.parametrize("W", [1, 2, 3, 4])
+@pytest.mark.parametrize("N", [1024, 1025, 1039, 4097, 20000, 100003])
+def test_streaming_decode_kernel_ragged_every_row(W, N):
+    """The cache-hit kernel proper (bf16, head dimension 128, at most four query rows, history of
+    1024 rows or more): partition tails of every residue, automatic and forced partition counts,
+    values and log-sum-exp of every row."""
+    w = ti.Workload(f"stream_decode_{W}_{N}", 2, 5, 128, N, W, ti.BF16, 1.0, 60601 + 31 * W + N)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = upload(host, w.dtype)
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    for s in (0, 1, 3, 16):
+        o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, num_splits=s, return_lse=True)
+        assert_close(o, ro, w.dtype, f"{w.name} splits {s}")
+        np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+    o32 = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, out_dtype=torch.float32)
+    assert_close(o32, ro, w.dtype, f"{w.name} f32 out")
+
+
+def test_streaming_decode_kernel_peaky_keys_and_strided_layout():
+    """Keys of very different sizes (one row in a hundred eight times larger: the reference point
+    of the online softmax moves late and far), on an interleaved-head layout."""
+    w = ti.Workload("stream_decode_peaky", 1, 6, 128, 30011, 2, ti.BF16, 1.0, 60707, peaky_mod=100, peaky_factor=8.0)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = upload(host, w.dtype)
+
+    def interleave(t):
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Q, Kh, Vh = (interleave(dev[k]) for k in ("Q", "Kh", "Vh"))
+    o, lse = tl.tlin_history_attn(Q, Kh, Vh, scale=w.scale, return_lse=True)
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    assert_close(o, ro, w.dtype, w.name)
+    np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+
+
 def test_decode_shape_at_the_papers_maximum_length():
     """Cache-hit step over 2^20 history rows (Section 6.4 runs sequences beyond one million
     tokens), 32 heads of dimension 128: 16 GiB of keys and values, every output row compared."""
