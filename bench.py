@@ -62,7 +62,8 @@ def parse():
                     help="also time the steps replayed from a HIP graph (ms_per_step_hip_graph): for the small, launch-bound workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemm-context", action="store_true",
-                    help="skip the library bf16 GEMM timed after the steps (context figure for matrix-core-bound workloads)")
+                    help="skip the context figures measured after the steps (shader clock while stepping; library bf16 "
+                         "GEMM for matrix-core-bound workloads; plain read stream for HBM-bound ones)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU work for the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy, so that a rocprofv3 --pmc run of this "
@@ -155,6 +156,56 @@ def gemm_context(torch, n=8192, iters=50):
                 "kind": "torch.matmul, same GPU, same run"}
     except Exception as e:                   # a context figure must never fail the bench
         return {"library_bf16_gemm_TFLOPs": None, "error": repr(e)}
+
+
+def read_ceiling(binding, buf, torch, iters=20):
+    """Context for HBM-bound workloads, never the peak: the rate at which this GPU feeds a kernel that
+    only reads (the library's measurement-aid stream kernel over the history keys, plain and
+    non-temporal loads), timed with events on the launch stream."""
+    try:
+        nbytes = buf.numel() * buf.element_size() if buf.is_contiguous() else 0
+        if nbytes < (256 << 20):
+            buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_()
+            nbytes = buf.numel()
+        st = torch.cuda.current_stream().cuda_stream
+        blocks_bytes = 16 * 8 * 256
+        read = nbytes // blocks_bytes * blocks_bytes
+        out = {"bytes": read, "kind": "libtlinattn stream-read kernel, same GPU, same run"}
+        for name, nt in (("plain_loads_GBs", False), ("nontemporal_loads_GBs", True)):
+            for _ in range(3):
+                binding.profile_stream_read(buf.data_ptr(), nbytes, nt, st)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                binding.profile_stream_read(buf.data_ptr(), nbytes, nt, st)
+            e1.record()
+            torch.cuda.synchronize()
+            out[name] = read / (e0.elapsed_time(e1) / iters * 1e-3) / 1e9
+        return out
+    except Exception as e:                   # a context figure must never fail the bench
+        return {"error": repr(e)}
+
+
+def sustained_clock(step, torch, seconds=1.2):
+    """Context: the shader clock rocm-smi reports while the step runs back to back (the chip is
+    power-limited under matrix-core load and settles well below its 2.4 GHz maximum).  None if
+    rocm-smi is not available."""
+    import re
+    import subprocess
+    try:
+        t_end = time.perf_counter() + seconds
+        proc = None
+        while time.perf_counter() < t_end or proc is None:
+            for _ in range(50):
+                step()
+            if proc is None and time.perf_counter() > t_end - seconds * 0.6:
+                proc = subprocess.Popen(["rocm-smi", "--showclocks"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
+            torch.cuda.synchronize()
+        text = proc.communicate(timeout=20)[0]
+        m = re.search(r"sclk clock level:[^(]*\((\d+)Mhz\)", text)
+        return int(m.group(1)) if m else None
+    except Exception:
+        return None
 
 
 def cpu_baseline(w, host, target_s, oracle, np, layer=True, joint=False):
@@ -335,7 +386,11 @@ def main():
     roof["frac_mfma"] = hist_tflops / peak_mfma
     roof["frac_hbm"] = hist_gbs / PEAK_HBM_GBS
     kname = "attn_f32" if w.dtype == ti.F32 else "attn_bf16"
+    # (tlin_history_attn runs bf16 calls with one or two query rows over 1024 or more rows of head
+    # dimension 128 in its streaming kernel)
+    streaming = not layer and w.dtype == ti.BF16 and w.D == 128 and w.W <= 2 and w.N >= 1024
     roof["kernel"] = (f"{kname}_pair_kernel (history partitions + window blocks)" if paired else
+                      "decode_bf16_kernel (history partitions, streamed through registers)" if streaming else
                       f"{kname}_kernel (history partitions)")
     roof["kernel_ms"] = hist_ms
     roof["traffic"], roof["traffic_source"] = measured_traffic(w.name)
@@ -355,10 +410,18 @@ def main():
         "kernels_ms": {"history": hist_ms, "window_causal": win_ms, "merge": merge_ms},
         "roofline": roof,
     }
-    if roof["bound"] == "mfma" and w.dtype != ti.F32 and not args.no_gemm_context:
-        out["context"] = gemm_context(torch)
-        if out["context"].get("library_bf16_gemm_TFLOPs"):
-            out["context"]["kernel_vs_library_gemm"] = hist_tflops / out["context"]["library_bf16_gemm_TFLOPs"]
+    if not args.no_gemm_context:
+        # context figures measured on the same GPU in the same run; never used as the peak
+        out["context"] = {"sclk_MHz_while_stepping": sustained_clock(step, torch), "sclk_MHz_max": 2400}
+        if roof["bound"] == "mfma" and w.dtype != ti.F32:
+            out["context"].update(gemm_context(torch))
+            if out["context"].get("library_bf16_gemm_TFLOPs"):
+                out["context"]["kernel_vs_library_gemm"] = hist_tflops / out["context"]["library_bf16_gemm_TFLOPs"]
+        if roof["bound"] == "hbm":
+            out["context"]["read_stream"] = read_ceiling(binding, Kh, torch)
+            best = out["context"]["read_stream"].get("nontemporal_loads_GBs")
+            if best:
+                out["context"]["kernel_vs_read_stream"] = hist_gbs / best
     if not args.no_cpu_baseline:
         import oracle
         rows, ref, out["cpu_baseline"] = cpu_baseline(w, host, args.cpu_seconds, oracle, np, layer, args.combine == "joint")

@@ -24,6 +24,13 @@ tlin_status tlin_profile_enable(int32_t enable);
  * and clears the record. */
 tlin_status tlin_profile_read(double ms[3], int64_t launches[3]);
 
+/* Enqueues a kernel that does nothing but read the first bytes (rounded down to a multiple of
+ * 32 KiB times the grid) of a device buffer of at least 1 MiB, 16-byte aligned, with plain
+ * (nontemporal == 0) or non-temporal loads: timed by the caller, it shows the read rate this GPU
+ * delivers to a kernel without any other work, the practical ceiling for the HBM-bound attention
+ * shapes.  The buffer is not modified. */
+tlin_status tlin_profile_stream_read(const void *buf, size_t bytes, int32_t nontemporal, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ TLIN_F32, TLIN_BF16 = 0, 1
 TLIN_COMBINE_SUM, TLIN_COMBINE_JOINT = 0, 1
 
 EXPORTS = ("tlin_workspace_bytes", "tlin_num_splits", "tlin_history_attn", "tlin_window_causal_attn",
-           "tlin_layer_attn", "tlin_layer_attn_static_ws", "tlin_slide_workspace_bytes", "tlin_slide_layer_attn", "tlin_profile_enable", "tlin_profile_read", "tlin_status_string", "tlin_version")
+           "tlin_layer_attn", "tlin_layer_attn_static_ws", "tlin_slide_workspace_bytes", "tlin_slide_layer_attn", "tlin_profile_enable", "tlin_profile_read", "tlin_profile_stream_read", "tlin_status_string", "tlin_version")
 
 
 class TlinParams(ctypes.Structure):
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.tlin_profile_enable.argtypes = [ctypes.c_int32]
         L.tlin_profile_read.restype = ctypes.c_int
         L.tlin_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        L.tlin_profile_stream_read.restype = ctypes.c_int
+        L.tlin_profile_stream_read.argtypes = [vp, sz, ctypes.c_int32, vp]
         L.tlin_status_string.restype = ctypes.c_char_p
         L.tlin_status_string.argtypes = [ctypes.c_int]
         L.tlin_version.restype = ctypes.c_int32
@@ -142,6 +144,11 @@ def slide_layer_attn_raw(p, q, kh, vh, kw, vw, o, ws, ws_bytes, stream) -> int:
 
 def profile_enable(on: bool) -> None:
     _check(int(lib().tlin_profile_enable(1 if on else 0)), "tlin_profile_enable")
+
+
+def profile_stream_read(addr: int, nbytes: int, nontemporal: bool, stream) -> None:
+    """Enqueue the read-only streaming kernel over a device buffer (measurement aid)."""
+    _check(int(lib().tlin_profile_stream_read(addr, nbytes, 1 if nontemporal else 0, stream)), "tlin_profile_stream_read")
 
 
 def profile_read():

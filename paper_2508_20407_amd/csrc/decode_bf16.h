@@ -38,6 +38,34 @@ __device__ __forceinline__ float dot2_bf16(unsigned a, unsigned b, float c)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, a), __builtin_bit_cast(dec_bf16x2, b), c, false);
 }
 
+// Measurement aid: a read stream with nothing else in it (every lane reads 16-byte pieces, folds them
+// and keeps the result), to show what this chip delivers to a kernel that only reads; the cache-hit
+// kernel is judged against it.  Reads the first 16 * pieces_per_block * gridDim.x bytes of buf.
+struct StreamReadArgs {
+    const void *buf;
+    size_t pieces_per_block;
+};
+template <bool NT>
+__global__ __launch_bounds__(256) void stream_read_kernel(const StreamReadArgs a)
+{
+    const u32x4 *q = (const u32x4 *)a.buf + (size_t)blockIdx.x * a.pieces_per_block;
+    unsigned acc = 0;
+    constexpr int UNR = 16;
+    size_t i = threadIdx.x;
+    for (; i + (UNR - 1) * 256 < a.pieces_per_block; i += 256 * UNR) {
+        u32x4 v[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) v[u] = NT ? __builtin_nontemporal_load(q + i + u * 256) : q[i + u * 256];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) acc += v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+    }
+    for (; i < a.pieces_per_block; i += 256) {
+        const u32x4 v = q[i];
+        acc += v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    asm volatile("" ::"v"(acc));       // the folded value is "used": the loads stay
+}
+
 // WQ: query rows computed (a.W <= WQ; rows past a.W repeat row 0 and are not stored).  Head
 // dimension 128.  Uses a.nsplit partitions of a.tiles_per_split * 64 key rows each.
 template <int WQ>
