@@ -497,6 +497,14 @@ void attn_bf16_kernel(const AttnArgs a)
     else attn_bf16_body<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, PAD>(a, blockIdx.x, gridDim.x);
 }
 
+// Resident key/value side with the in-wave pipeline (an even number T1 of key tiles).
+template <int D, int T1, int TMAX, bool PAD = false>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(1, 8)))
+void attn_bf16_resident_pipe_kernel(const AttnArgs a)
+{
+    attn_bf16_resident_pipe_body<D, 8, PAD, T1, TMAX>(a, blockIdx.x, gridDim.x);
+}
+
 // History partition blocks and window causal blocks of one call in a single launch.
 template <int D, int NW, int NSTAGE, bool PAD = false, bool NT = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE == 2 && NW < 8 ? 2 : 1, 8)))

@@ -22,7 +22,15 @@
 // slots ahead, a few vector instructions), so both pipes of the SIMD are busy at the same time
 // within one wave, and the second wave of the SIMD fills what is left.  The weights of tile n are
 // taken against the reference point that was fixed at the end of step n-1, which is the same
-// point the classic order uses: results are identical up to the order of the additions into l.
+// point the classic order uses.
+//
+// The row sum l is accumulated from the fp32 weights with plain adds, not with v_dot2_f32_bf16 on
+// the rounded ones as attn_bf16_body does: under a stream of matrix instructions a dot2 costs about
+// 6 cycles of the matrix pipe (it does not execute beside it), an add costs nothing (measured on a
+// single-wave stream: 42 against 34 cycles per matrix instruction with this softmax work in
+// between).  The normaliser is then the exact sum of the weights while the value product uses their
+// bf16 roundings, so a row is a convex combination only to within 2^-9 per weight; the difference
+// stays far inside the tolerance and the log-sum-exp output becomes exact to fp32 rounding.
 //
 // Ring of two tiles for K and two for V; K runs one tile ahead of V.  Step n reads K(n+1) and
 // V(n); at its top (after the step's single barrier) every wave has finished K(n) and V(n-1),
@@ -170,7 +178,6 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
     const float thr = 8.0f / a.c;          // reference point moves only beyond 2^8 (see attn_bf16_body)
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     float mc = 0.f;                        // m * c of the current reference point
     bf16x8 pb[2][2];                       // weights of the current tile, B-operand order
 
@@ -187,17 +194,17 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
         const bf16x8 kf = *(lds_bf16x8 *)(uintptr_t)(kaddr[s] + kstage * TILE_B + kk * (32 * ROWB));
         S[kk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], S[kk], 0, 0, 0);
     };
-    // weights of the 16 keys of quarter (kb, t2) from S (against mc), their row sum into l
+    // weights of the 16 keys of quarter (kb, t2) from S (against mc), rounded to bf16 for the value
+    // product; their fp32 values are summed into l
     auto weights_q = [&](const f32x16 (&S)[2], int kb, int t2) __attribute__((always_inline)) {
         float ls = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            const __bf16 p0 = (__bf16)fast_exp2(fmaf(S[kb][8 * t2 + e], a.c, -mc));
-            const __bf16 p1 = (__bf16)fast_exp2(fmaf(S[kb][8 * t2 + e + 1], a.c, -mc));
-            pb[kb][t2][e] = p0;
-            pb[kb][t2][e + 1] = p1;
-            const bf16x2 pp = {p0, p1};
-            ls = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ls, false);
+            const float p0 = fast_exp2(fmaf(S[kb][8 * t2 + e], a.c, -mc));
+            const float p1 = fast_exp2(fmaf(S[kb][8 * t2 + e + 1], a.c, -mc));
+            pb[kb][t2][e] = (__bf16)p0;
+            pb[kb][t2][e + 1] = (__bf16)p1;
+            ls += p0 + p1;
         }
         l += ls;
     };
@@ -270,6 +277,20 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
     constexpr int PIPE_VPF = 2;       // V operands (two reads each) requested ahead of their product
     constexpr int PIPE_WA = 2;        // quarters of the tile's weights computed in phase A (the rest in phase B)
     constexpr bool PIPE_PACED = true; // tile loads spread over phase A instead of a burst behind the barrier
+    constexpr int VPQ = 29;           // vector instructions per quarter of a tile's weights: 8 fma, 8 exp2, 4 convert, 9 add
+
+    // value product number i of a tile (i = 8 kb + 4 t2 + db): its V operand, and the product
+    auto v_read = [&](int i, int vstage) __attribute__((always_inline)) {
+        const int kb = i / (2 * DB), t2 = (i / DB) % 2, db = i % DB;
+        const unsigned ad = vaddr[db] + vstage * TILE_B + (kb * 32 + 16 * t2) * ROWB;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(uintptr_t)ad);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(uintptr_t)(ad + 8 * ROWB));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto pv_op = [&](int i, bf16x8 vf) __attribute__((always_inline)) {
+        const int kb = i / (2 * DB), t2 = (i / DB) % 2, db = i % DB;
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kb][t2], oacc[db], 0, 0, 0);
+    };
 
     // One step with compile-time ring stages: reads K(n+1) from stage KST, V(n) from stage VST.
     auto step = [&](const f32x16 (&Sc)[2], f32x16 (&Sn)[2], int n, auto kst, auto vst) __attribute__((always_inline)) {
@@ -299,23 +320,27 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
 #pragma unroll
         for (int q = 0; q < PIPE_WA; ++q) asm volatile("" : "+v"(pb[q >> 1][q & 1]));
         asm volatile("" : "+v"(l));
+        // (tried and within noise: the first value operands of phase B requested at the end of this
+        // phase; some of the vector instructions ahead of the first product)
 #pragma unroll
         for (int i = 0; i < PIPE_KPF; ++i) __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
         static_for<2 * DS>([&](auto ic) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
             __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
             if (i + PIPE_KPF < 2 * DS) __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
-            // 24 vector instructions per quarter, spread evenly over the products
-            constexpr int nv = (24 * PIPE_WA * (i + 1)) / (2 * DS) - (24 * PIPE_WA * i) / (2 * DS);
+            // the phase's vector instructions, spread evenly over the products
+            constexpr int nv = (VPQ * PIPE_WA * (i + 1)) / (2 * DS) - (VPQ * PIPE_WA * i) / (2 * DS);
             if (nv > 0) __builtin_amdgcn_sched_group_barrier(SG_VALU | SG_TRANS, nv, 0);
         });
         __builtin_amdgcn_sched_barrier(0);
         if ((t0 + n + 2) * BN > NK) mask_ragged(Sn, (t0 + n + 1) * BN);
         // phase B
-        pv_half(0, VST);
+#pragma unroll
+        for (int i = 0; i < 2 * DB; ++i) pv_op(i, v_read(i, VST));
 #pragma unroll
         for (int q = PIPE_WA; q < 4; ++q) weights_q(Sc, q >> 1, q & 1);
-        pv_half(1, VST);
+#pragma unroll
+        for (int i = 2 * DB; i < 4 * DB; ++i) pv_op(i, v_read(i, VST));
         const float mx = row_max(Sn);
 #pragma unroll
         for (int i = 0; i < 2 * PIPE_VPF; ++i) __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 1);
@@ -324,7 +349,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
             __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 1);
             if (i + PIPE_VPF < 4 * DB) __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 1);
             // the remaining quarters' weights during the first half's products, the row maximum after them
-            constexpr int nv = i < 2 * DB ? (24 * (4 - PIPE_WA) * (i + 1)) / (2 * DB) - (24 * (4 - PIPE_WA) * i) / (2 * DB) : 3;
+            constexpr int nv = i < 2 * DB ? (VPQ * (4 - PIPE_WA) * (i + 1)) / (2 * DB) - (VPQ * (4 - PIPE_WA) * i) / (2 * DB) : 3;
             if (nv > 0) __builtin_amdgcn_sched_group_barrier(SG_VALU | SG_TRANS, nv, 1);
         });
         __builtin_amdgcn_sched_barrier(0);
@@ -423,6 +448,299 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
             a.Mpart[slot * a.W + row] = m * a.c;
             a.Lpart[slot * a.W + row] = lt;
         }
+    }
+}
+
+// The same in-wave pipeline for the shape whose QUERY side is the long one (Section 3, last layer of
+// the context path: every history row queries the few compressed rows): all T1 key tiles stay in
+// LDS for the lifetime of the workgroup, which walks over query blocks qb, qb + q_groups, ... without
+// any barrier, each block running the pipeline over the resident tiles (T1 is even, so the two score
+// accumulators keep their roles from block to block).  Direct output only (one partition).
+template <int D, int NW, bool PAD, int T1, int TMAX>
+__device__ __forceinline__ void attn_bf16_resident_pipe_body(const AttnArgs &a, int bid, int nblocks)
+{
+    static_assert(T1 % 2 == 0 && T1 >= 2 && T1 <= TMAX, "an even number of resident key tiles");
+    constexpr int BN = 64, BM = NW * 32, ROWB = D * 2, TILE_B = BN * ROWB, CPR = ROWB / 16, RPI = 1024 / ROWB;
+    constexpr int NDMA = BN / RPI / NW, DS = D / 16, DB = D / 32;
+    static_assert(BN % (RPI * NW) == 0 && NDMA >= 1, "tile does not divide over the waves");
+    static_assert((TMAX - 1) * TILE_B + 56 * ROWB + 256 <= 65536, "LDS offsets must fit the 16-bit immediate");
+
+    char *const Ks = tlin_smem;
+    char *const Vs = tlin_smem + TMAX * TILE_B;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane & 31, h = lane >> 5;
+
+    const int L = xcd_remap(bid, nblocks);
+    const int qstep = a.q_groups;
+    const Problem pr = decode_problem<BM, BN, false>(a, L, qstep);
+    if (pr.skip) return;
+    int qb = pr.qb;
+    const int bh = pr.bh, b = bh / a.H, hd = bh % a.H;
+    const int Wq = pr.W, NK = pr.NK;
+    const bool ragged = NK < T1 * BN;
+
+    const int64_t k_rb = a.k_sr * 2, v_rb = a.v_sr * 2;
+    const __bf16 *Qg = (const __bf16 *)a.Q + (int64_t)b * a.q_sb + (int64_t)hd * a.q_sh;
+    const char *Kg = (const char *)((const __bf16 *)a.K + (int64_t)b * a.k_sb + (int64_t)hd * a.k_sh);
+    const char *Vg = (const char *)((const __bf16 *)a.V + (int64_t)b * a.v_sb + (int64_t)hd * a.v_sh);
+
+    const int dchunks = PAD ? (a.D + 7) >> 3 : D / 8;
+    const int straddle = (PAD && (a.D & 7)) ? (a.D >> 4) : -1;
+    auto clip = [&](bf16x8 f) __attribute__((always_inline)) {
+        const int keep = a.D - (16 * straddle + 8 * h);
+        u32x4 u = __builtin_bit_cast(u32x4, f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u[e] &= keep >= 2 * e + 2 ? ~0u : keep == 2 * e + 1 ? 0x0000ffffu : 0u;
+        return __builtin_bit_cast(bf16x8, u);
+    };
+    // Q^T fragments of the 32 rows this wave owns in query block `blk`
+    auto load_q = [&](bf16x8 (&q)[DS], int blk) __attribute__((always_inline)) {
+        const int r = min(blk * BM + wave * 32 + j, Wq - 1);
+        const __bf16 *qp = Qg + (int64_t)r * a.q_sr + 8 * h;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            if (PAD && 16 * s + 8 * h >= a.D) { q[s] = bf16x8{}; continue; }
+            const bf16x8 f = *(const bf16x8 *)(qp + 16 * s);
+            q[s] = (PAD && s == straddle) ? clip(f) : f;
+        }
+    };
+
+    // ---- the whole key/value side into LDS, once: tile t lives in stage t
+    {
+        const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_offset(Ks) + wave * (NDMA * 1024));
+#pragma unroll
+        for (int t = 0; t < T1; ++t) {
+            const int key0 = t * BN;
+            const int rows = min(BN, NK - key0);
+            const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
+            const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
+#pragma unroll
+            for (int i = 0; i < NDMA; ++i) {
+                const int drow = (wave * NDMA + i) * RPI + lane / CPR;
+                int kc = (lane % CPR) ^ Swz<D>::k(drow), vc = (lane % CPR) ^ Swz<D>::v(drow);
+                if (PAD && kc >= dchunks) kc = 0;
+                if (PAD && vc >= dchunks) vc = 0;
+                direct_load_1k(kd, (unsigned)(drow * k_rb) + (kc << 4), lds_wave + t * TILE_B + i * 1024);
+                direct_load_1k(vd, (unsigned)(drow * v_rb) + (vc << 4), lds_wave + (TMAX + t) * TILE_B + i * 1024);
+            }
+        }
+    }
+    bf16x8 qf[DS];
+    load_q(qf, qb);
+    wait_vmcnt<0>();
+    if (PAD && (a.D & 7)) {
+        // the part from a.D on of the K chunk that straddles a.D is cleared by the wave that loaded the row
+        if (lane < NDMA * RPI) {
+            const int r = (wave * NDMA + lane / RPI) * RPI + lane % RPI;
+            const int pos = (a.D >> 3) ^ Swz<D>::k(r);
+#pragma unroll
+            for (int t = 0; t < T1; ++t) *(u32x2 *)(Ks + t * TILE_B + r * ROWB + (pos << 4) + 8) = u32x2{0u, 0u};
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+    __builtin_amdgcn_s_barrier();
+
+    const int i16 = lane & 15, blk1 = (lane >> 4) & 1;
+    unsigned kaddr[DS], vaddr[DB];
+#pragma unroll
+    for (int s = 0; s < DS; ++s) kaddr[s] = lds_offset(Ks) + j * ROWB + (((2 * s + h) ^ Swz<D>::k(j)) << 4);
+    {
+        const int r0 = 4 * h + (i16 >> 2);
+        const int sw = Swz<D>::v(r0) << 4;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) vaddr[db] = lds_offset(Vs) + r0 * ROWB + ((64 * db + 32 * blk1 + 8 * (i16 & 3)) ^ sw);
+    }
+
+    f32x16 oacc[DB];
+    float m = -INFINITY, l = 0.f, mc = 0.f;
+    auto reset = [&]() __attribute__((always_inline)) {
+        l = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+    };
+    reset();
+    const float thr = 8.0f / a.c;
+    bf16x8 pb[2][2];
+    typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+
+    // ---- pieces of a step (as in attn_bf16_pipe_body)
+    auto qk_zero = [&](f32x16 (&S)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) S[kk][v] = 0.f;
+    };
+    auto qk_tile = [&](f32x16 (&S)[2], const bf16x8 (&q)[DS], int tile) __attribute__((always_inline)) {
+        qk_zero(S);
+#pragma unroll
+        for (int s = 0; s < DS; ++s)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 kf = *(lds_bf16x8 *)(uintptr_t)(kaddr[s] + tile * TILE_B + kk * (32 * ROWB));
+                S[kk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q[s], S[kk], 0, 0, 0);
+            }
+    };
+    auto weights_q = [&](const f32x16 (&S)[2], int kb, int t2) __attribute__((always_inline)) {
+        float ls = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = fast_exp2(fmaf(S[kb][8 * t2 + e], a.c, -mc));
+            const float p1 = fast_exp2(fmaf(S[kb][8 * t2 + e + 1], a.c, -mc));
+            pb[kb][t2][e] = (__bf16)p0;
+            pb[kb][t2][e + 1] = (__bf16)p1;
+            ls += p0 + p1;
+        }
+        l += ls;
+    };
+    auto pv_half = [&](int kb, int tile) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const unsigned ad = vaddr[db] + tile * TILE_B + (kb * 32 + 16 * t2) * ROWB;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(uintptr_t)ad);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(uintptr_t)(ad + 8 * ROWB));
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kb][t2], oacc[db], 0, 0, 0);
+            }
+    };
+    auto mask_ragged = [&](f32x16 (&S)[2], int key0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = key0 + kb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (key >= NK) S[kb][v] = -INFINITY;
+            }
+        asm volatile("" ::: "memory");
+    };
+    auto row_max = [&](const f32x16 (&S)[2]) __attribute__((always_inline)) {
+        float mx = S[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, S[kb][v]);
+        return xhalf_max(mx);
+    };
+    auto move_reference = [&](float mx) __attribute__((always_inline)) {
+        if (__builtin_amdgcn_ballot_w64(mx > m + thr) != 0) {
+            const float mn = fmaxf(m, mx);
+            const float alpha = (mn == -INFINITY) ? 1.f : fast_exp2((m - mn) * a.c);
+            l *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+            m = mn;
+            mc = (m == -INFINITY) ? 0.f : m * a.c;
+        }
+    };
+    // normalise and store the block's rows
+    auto finish_block = [&](int blk) __attribute__((always_inline)) {
+        const float lt = xhalf_sum(l);
+        const int row = blk * BM + wave * 32 + j;
+        if (row < Wq) {
+            const float inv = 1.0f / lt;
+            const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)row * a.o_sr;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int d = 32 * db + 8 * g + 4 * h;
+                    if (PAD && d >= a.D) continue;
+                    f32x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = oacc[db][4 * g + e] * inv;
+                    if (a.out_bf16) {
+                        bf16x4 ob;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ob[e] = (__bf16)o[e];
+                        *(bf16x4 *)((__bf16 *)a.O + off + d) = ob;
+                    } else {
+                        *(f32x4 *)((float *)a.O + off + d) = o;
+                    }
+                }
+            if (a.lse && h == 0) a.lse[(int64_t)bh * a.W + row] = m * a.scale + logf(lt);
+        }
+    };
+
+    constexpr int KPF = 4, VPF = 2;
+    constexpr int VPQ = 29;
+    // phase A: scores of key tile KT with the queries q into Sn, weights of the first two quarters of Sc
+    auto phase_a = [&](const f32x16 (&Sc)[2], f32x16 (&Sn)[2], const bf16x8 (&q)[DS], auto kt) __attribute__((always_inline)) {
+        constexpr int KT = decltype(kt)::value;
+        qk_tile(Sn, q, KT);
+        weights_q(Sc, 0, 0);
+        weights_q(Sc, 0, 1);
+        asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]), "+v"(l));
+#pragma unroll
+        for (int i = 0; i < KPF; ++i) __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
+        static_for<2 * DS>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+            if (i + KPF < 2 * DS) __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
+            constexpr int nv = (2 * VPQ * (i + 1)) / (2 * DS) - (2 * VPQ * i) / (2 * DS);
+            if (nv > 0) __builtin_amdgcn_sched_group_barrier(SG_VALU | SG_TRANS, nv, 0);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        if (KT == T1 - 1 && ragged) mask_ragged(Sn, KT * BN);
+    };
+    // phase B: value products of tile VT with the weights of Sc (second half computed here), row maximum of Sn
+    auto phase_b = [&](const f32x16 (&Sc)[2], const f32x16 (&Sn)[2], auto vt) __attribute__((always_inline)) {
+        constexpr int VT = decltype(vt)::value;
+        pv_half(0, VT);
+        weights_q(Sc, 1, 0);
+        weights_q(Sc, 1, 1);
+        pv_half(1, VT);
+        const float mx = row_max(Sn);
+#pragma unroll
+        for (int i = 0; i < 2 * VPF; ++i) __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 1);
+        static_for<4 * DB>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 1);
+            if (i + VPF < 4 * DB) __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 1);
+            constexpr int nv = i < 2 * DB ? (2 * VPQ * (i + 1)) / (2 * DB) - (2 * VPQ * i) / (2 * DB) : 3;
+            if (nv > 0) __builtin_amdgcn_sched_group_barrier(SG_VALU | SG_TRANS, nv, 1);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        return mx;
+    };
+
+    // ---- per query block: scores of tile 0, T1 - 1 pipelined steps, the last tile's weights and
+    // value products, normalise and store.  The next block's queries are requested into the same
+    // registers right behind their last use (the score products of the last key tile), and have the
+    // rest of the block to arrive; the other wave of the SIMD, which is at another point of its own
+    // block (there are no barriers here), fills the unpipelined head and tail of this one.
+    f32x16 S0[2], S1[2];
+    while (true) {
+        qk_tile(S0, qf, 0);
+        if (T1 == 1 && ragged) mask_ragged(S0, 0);
+        m = row_max(S0);
+        mc = (m == -INFINITY) ? 0.f : m * a.c;
+        const bool has_next = qb + qstep < a.nqb;      // uniform over the workgroup
+        static_for<T1 - 1>([&](auto nc) __attribute__((always_inline)) {
+            constexpr int n = decltype(nc)::value;
+            if constexpr (n % 2 == 0) phase_a(S0, S1, qf, std::integral_constant<int, n + 1>{});
+            else phase_a(S1, S0, qf, std::integral_constant<int, n + 1>{});
+            if (n == T1 - 2 && has_next) load_q(qf, qb + qstep);
+            if constexpr (n % 2 == 0) move_reference(phase_b(S0, S1, nc));
+            else move_reference(phase_b(S1, S0, nc));
+        });
+        // last tile (scores in S1, T1 being even)
+        weights_q(S1, 0, 0);
+        weights_q(S1, 0, 1);
+        pv_half(0, T1 - 1);
+        weights_q(S1, 1, 0);
+        weights_q(S1, 1, 1);
+        pv_half(1, T1 - 1);
+        finish_block(qb);
+        if (!has_next) break;
+        reset();
+        qb += qstep;
     }
 }
 

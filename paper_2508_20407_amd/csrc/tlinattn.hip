@@ -352,6 +352,19 @@ tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
     return launch_bf16_shape_pad<D, NW, QB, CAUSAL, NSTAGE, RESIDENT, false>(a, grid, st);
 }
 
+template <int D, int T1, int TMAX>
+tlin_status launch_resident_pipe(const AttnArgs &a, int grid, hipStream_t st)
+{
+    constexpr int lds_bytes = 2 * TMAX * 64 * D * 2;
+    static_assert(lds_bytes <= 160 * 1024, "resident tiles exceed the 160 KB of a gfx950 compute unit");
+    static std::atomic<uint64_t> lds_allowed[2] = {{0}, {0}};
+    const bool pad = a.D != D;
+    const void *kernel = pad ? (const void *)attn_bf16_resident_pipe_kernel<D, T1, TMAX, true>
+                             : (const void *)attn_bf16_resident_pipe_kernel<D, T1, TMAX, false>;
+    if (allow_lds(kernel, lds_bytes, lds_allowed[pad]) != TLIN_OK) return TLIN_ERR_HIP;
+    return launch_kernel(kernel, dim3(grid), dim3(512), lds_bytes, st, a);
+}
+
 // Ring depth per kernel shape (measured): a compute unit keeps little more than one tile of loads
 // in flight, so a deep ring only makes waves wait at the issue of loads that cannot start yet.  Two
 // stages also let two of the smaller workgroups share a compute unit.
@@ -424,6 +437,10 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
         const int64_t grid64 = bh * g;
         if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
         LaunchTimer timer(KC_HISTORY, st);
+        // an even number of key tiles at head dimension 128: the pipelined variant
+        const int ntiles = (a.NK + 63) / 64;
+        if (dpad(p->D) == 128 && ntiles == 4) return launch_resident_pipe<128, 4, 4>(a, (int)grid64, st);
+        if (dpad(p->D) == 128 && ntiles == 2) return launch_resident_pipe<128, 2, 4>(a, (int)grid64, st);
         return dpad(p->D) == 128 ? launch_bf16_shape<128, 8, 1, false, 4, true>(a, (int)grid64, st)
                                  : launch_bf16_shape<64, 8, 1, false, 8, true>(a, (int)grid64, st);
     }
