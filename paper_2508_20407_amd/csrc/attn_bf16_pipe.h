@@ -54,7 +54,11 @@ __device__ __forceinline__ void static_for_seq(F &&f, std::integer_sequence<int,
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F &&f) { static_for_seq(f, std::make_integer_sequence<int, N>{}); }
 
-template <int D, int NW, bool PAD, bool NT>
+// CAUSAL: the window's causal attention (query i sees keys j <= i; Section 3, Causal attention).  A
+// workgroup walks the key tiles up to its last row; a wave leaves the pipeline after the tile that
+// holds its own rows' diagonal (later tiles lie after every row it owns) and from then on only meets
+// the barriers and issues its share of the tile loads.
+template <int D, int NW, bool PAD, bool NT, bool CAUSAL = false>
 __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, int nblocks)
 {
     constexpr int NSTAGE = 2;
@@ -78,14 +82,14 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
     const int j = lane & 31, h = lane >> 5;
 
     const int L = xcd_remap(bid, nblocks);
-    const Problem pr = decode_problem<BM, BN, false>(a, L, a.nqb);
+    const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, a.nqb);
     if (pr.skip) return;                               // uniform over the workgroup
     const int qb = pr.qb, split = pr.split, bh = pr.bh;
     const int b = bh / a.H, hd = bh % a.H;
     const int Wq = pr.W, NK = pr.NK;
 
-    const int t0 = split * pr.tps;
-    const int t1 = min(t0 + pr.tps, (NK + BN - 1) / BN);
+    const int t0 = CAUSAL ? 0 : split * pr.tps;
+    const int t1 = CAUSAL ? (min(NK, qb * BM + BM) + BN - 1) / BN : min(t0 + pr.tps, (NK + BN - 1) / BN);
     const int nt = t1 - t0;                            // tiles of this partition (may be <= 0 in the sliding schedule)
 
     const int64_t k_rb = a.k_sr * 2, v_rb = a.v_sr * 2;
@@ -105,6 +109,8 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
     };
 
     const int qrow0 = qb * BM + wave * 32;
+    // the last tile this wave computes on (uniform over the wave): causal, the tile of its rows' diagonal
+    const int tl = CAUSAL ? min((qrow0 + 31) / BN, nt - 1) : nt - 1;
     bf16x8 qf[DS];     // Q^T fragments (B operand): lane holds query j, contraction elements 16*s + 8*h .. +7
     {
         const int r = min(qrow0 + j, Wq - 1);
@@ -225,16 +231,20 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
                 oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kb][t2], oacc[db], 0, 0, 0);
             }
     };
+    // keys past the end of the tensor and (causal) keys after the query row
     auto mask_ragged = [&](f32x16 (&S)[2], int key0) __attribute__((always_inline)) {
+        const int lim = CAUSAL ? min(qrow0 + j, NK - 1) : NK - 1;     // last visible key
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int key = key0 + kb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (key >= NK) S[kb][v] = -INFINITY;
+                if (key > lim) S[kb][v] = -INFINITY;
             }
         asm volatile("" ::: "memory");     // stays a branch around these selects (taken once per partition at most)
     };
+    // does local tile nn need the mask: ragged end of the tensor, or the wave's diagonal tile
+    auto needs_mask = [&](int nn) __attribute__((always_inline)) { return (t0 + nn + 1) * BN > NK || (CAUSAL && nn == tl); };
     auto row_max = [&](const f32x16 (&S)[2]) __attribute__((always_inline)) {
         float mx = S[0][0];
 #pragma unroll
@@ -298,9 +308,20 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
         wait_vmcnt<0>();
         scrub(KST);
         __builtin_amdgcn_s_barrier();
-        if (!PIPE_PACED) {
+        if (!PIPE_PACED || (CAUSAL && n + 1 > tl)) {
 #pragma unroll
             for (int i = 0; i < 2 * NDMA; ++i) dma(i, n, VST, KST);
+        }
+        if (CAUSAL && n + 1 > tl) {
+            // this wave has no further tile to score: tile n is its last one (weights and value
+            // products, unpipelined) or already behind it
+            if (n == tl) {
+                weights(Sc, 0);
+                pv_half(0, VST);
+                weights(Sc, 1);
+                pv_half(1, VST);
+            }
+            return;
         }
         // phase A
         qk_zero(Sn);
@@ -333,7 +354,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
             if (nv > 0) __builtin_amdgcn_sched_group_barrier(SG_VALU | SG_TRANS, nv, 0);
         });
         __builtin_amdgcn_sched_barrier(0);
-        if ((t0 + n + 2) * BN > NK) mask_ragged(Sn, (t0 + n + 1) * BN);
+        if (needs_mask(n + 1)) mask_ragged(Sn, (t0 + n + 1) * BN);
         // phase B
 #pragma unroll
         for (int i = 0; i < 2 * DB; ++i) pv_op(i, v_read(i, VST));
@@ -375,7 +396,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
             qk_step(S0, s, 0, 0);
             qk_step(S0, s, 1, 0);
         }
-        if ((t0 + 1) * BN > NK) mask_ragged(S0, t0 * BN);
+        if (needs_mask(0)) mask_ragged(S0, t0 * BN);
         move_reference(row_max(S0));
 
         // step n reads K(n+1) from stage (n+1) % 2 and V(n) from stage n % 2
@@ -393,7 +414,9 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
         // last tile (n = nt - 1, in S0): weights and value products only
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (n & 1) {
+        if (CAUSAL && tl < nt - 1) {
+            // this wave finished with an earlier tile
+        } else if (n & 1) {
             weights(S0, 0);
             pv_half(0, 1);
             weights(S0, 1);
@@ -433,7 +456,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
             }
         if (a.lse && h == 0) a.lse[(int64_t)bh * a.W + row] = m * a.scale + logf(lt);
     } else {
-        const int64_t slot = pr.slot + a.part0 + split;
+        const int64_t slot = pr.slot + a.part0 + (CAUSAL ? 0 : split);
         float *op = a.Opart + (slot * a.W + row) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)

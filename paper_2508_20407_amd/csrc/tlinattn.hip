@@ -371,7 +371,7 @@ tlin_status launch_resident_pipe(const AttnArgs &a, int grid, hipStream_t st)
 template <int D, bool CAUSAL>
 tlin_status launch_bf16(const AttnArgs &a, Shape s, int grid, hipStream_t st)
 {
-    constexpr int NS = CAUSAL ? 4 : 2;
+    constexpr int NS = (CAUSAL && D != 128) ? 4 : 2;
     if (s.nw == 8) return launch_bf16_shape<D, 8, 1, CAUSAL, NS>(a, grid, st);
     if (s.nw == 4) return launch_bf16_shape<D, 4, 1, CAUSAL, NS>(a, grid, st);
     return launch_bf16_shape<D, 2, 1, CAUSAL, NS>(a, grid, st);
