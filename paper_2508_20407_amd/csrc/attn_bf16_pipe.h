@@ -663,11 +663,44 @@ __device__ __forceinline__ void attn_bf16_resident_pipe_body(const AttnArgs &a, 
         }
     };
     // normalise and store the block's rows
+    // bf16 output goes through a wave-private 4 KB staging area behind the resident tiles: a lane owns
+    // one row and would store it as sixteen 8-byte pieces, each instruction touching 32 rows; turned
+    // through LDS (half a row at a time, 16-byte chunk ^ (row / 2 & 7) keeps writes and reads off each
+    // other's banks) a store instruction writes eight rows' 128-byte halves whole.
+    constexpr bool STAGED = !PAD && (2 * TMAX * TILE_B + NW * 4096 <= 160 * 1024) && D == 128;
+    char *const stg = tlin_smem + 2 * TMAX * TILE_B + wave * 4096;
     auto finish_block = [&](int blk) __attribute__((always_inline)) {
         const float lt = xhalf_sum(l);
-        const int row = blk * BM + wave * 32 + j;
+        const int row0 = blk * BM + wave * 32;
+        const int row = row0 + j;
+        const float inv = 1.0f / lt;
+        if (STAGED && a.out_bf16) {
+            const int64_t obase = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh;
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+#pragma unroll
+                for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int db = 2 * hf + dd;
+                        bf16x4 ob;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ob[e] = (__bf16)(oacc[db][4 * g + e] * inv);
+                        const int ch = 4 * dd + g;       // 16-byte chunk of the 128-byte half row; this lane holds its half h
+                        *(bf16x4 *)(stg + j * 128 + ((ch ^ ((j >> 1) & 7)) << 4) + 8 * h) = ob;
+                    }
+                // the wave reads what its own lanes wrote: LDS operations of a wave complete in order
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int r = (lane >> 3) + 8 * k, cc = lane & 7;
+                    const u32x4 piece = *(const u32x4 *)(stg + r * 128 + ((cc ^ ((r >> 1) & 7)) << 4));
+                    if (row0 + r < Wq) *(u32x4 *)((__bf16 *)a.O + obase + (int64_t)(row0 + r) * a.o_sr + 64 * hf + 8 * cc) = piece;
+                }
+            }
+            if (row < Wq && a.lse && h == 0) a.lse[(int64_t)bh * a.W + row] = m * a.scale + logf(lt);
+            return;
+        }
         if (row < Wq) {
-            const float inv = 1.0f / lt;
             const int64_t off = (int64_t)b * a.o_sb + (int64_t)hd * a.o_sh + (int64_t)row * a.o_sr;
 #pragma unroll
             for (int db = 0; db < DB; ++db)

@@ -355,7 +355,8 @@ tlin_status launch_bf16_shape(const AttnArgs &a, int grid, hipStream_t st)
 template <int D, int T1, int TMAX>
 tlin_status launch_resident_pipe(const AttnArgs &a, int grid, hipStream_t st)
 {
-    constexpr int lds_bytes = 2 * TMAX * 64 * D * 2;
+    // the resident tiles and, behind them, 4 KB per wave for turning the output rows
+    constexpr int lds_bytes = 2 * TMAX * 64 * D * 2 + 8 * 4096;
     static_assert(lds_bytes <= 160 * 1024, "resident tiles exceed the 160 KB of a gfx950 compute unit");
     static std::atomic<uint64_t> lds_allowed[2] = {{0}, {0}};
     const bool pad = a.D != D;
