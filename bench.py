@@ -449,10 +449,10 @@ def main():
 # sources are the ones it was measured on (csrc_sha16 below = kernel_sources_sha16() at that time);
 # otherwise `traffic` is null and `traffic_source` says why.
 MEASURED_TRAFFIC = {
-    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_884.3 * 2.0 * 1024) + 41_600 * 1024,   # 2.016 GiB fetched + 40.6 MiB written
-                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "unset"},
-    "decode_bf16_N131072_W1": {"bytes": int(1_048_648.7 * 2.0 * 1024) + 260 * 1024,      # 2.0001 GiB fetched + 260 KiB written
-                               "profile": "profiles/attn_bf16_history_decode_w1.md", "csrc_sha16": "unset"},
+    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_961.3 * 2.0 * 1024) + int(41_600.2 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
+                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "184b26937bdd4d6f"},
+    "decode_bf16_N131072_W1": {"bytes": int(1_055_853.9 * 2.0 * 1024) + int(576.4 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
+                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": "184b26937bdd4d6f"},
 }
 
 
