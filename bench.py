@@ -386,11 +386,12 @@ def main():
     roof["frac_mfma"] = hist_tflops / peak_mfma
     roof["frac_hbm"] = hist_gbs / PEAK_HBM_GBS
     kname = "attn_f32" if w.dtype == ti.F32 else "attn_bf16"
-    # (tlin_history_attn runs bf16 calls with one or two query rows over 1024 or more rows of head
-    # dimension 128 in its streaming kernel)
-    streaming = not layer and w.dtype == ti.BF16 and w.D == 128 and w.W <= 2 and w.N >= 1024
+    # (tlin_history_attn runs calls with few query rows over 1024 or more history rows in its
+    # streaming kernel: bf16 at head dimension 128 up to two rows, fp32 up to eight)
+    streaming = not layer and w.N >= 1024 and ((w.dtype == ti.BF16 and w.D == 128 and w.W <= 2) or
+                                               (w.dtype == ti.F32 and w.W <= 8))
     roof["kernel"] = (f"{kname}_pair_kernel (history partitions + window blocks)" if paired else
-                      "decode_bf16_kernel (history partitions, streamed through registers)" if streaming else
+                      "decode_kernel (history partitions, streamed through registers)" if streaming else
                       f"{kname}_kernel (history partitions)")
     roof["kernel_ms"] = hist_ms
     roof["traffic"], roof["traffic_source"] = measured_traffic(w.name)
@@ -449,10 +450,10 @@ def main():
 # sources are the ones it was measured on (csrc_sha16 below = kernel_sources_sha16() at that time);
 # otherwise `traffic` is null and `traffic_source` says why.
 MEASURED_TRAFFIC = {
-    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_961.3 * 2.0 * 1024) + int(41_600.2 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
-                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "184b26937bdd4d6f"},
-    "decode_bf16_N131072_W1": {"bytes": int(1_055_853.9 * 2.0 * 1024) + int(576.4 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
-                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": "184b26937bdd4d6f"},
+    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_969.5 * 2.0 * 1024) + int(41_600.8 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
+                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "61e42faa2a1b66f7"},
+    "decode_bf16_N131072_W1": {"bytes": int(1_055_842.6 * 2.0 * 1024) + int(576.2 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
+                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": "61e42faa2a1b66f7"},
 }
 
 

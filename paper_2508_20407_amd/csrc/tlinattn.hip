@@ -13,7 +13,7 @@
 
 #include "attn_bf16.h"
 #include "attn_f32.h"
-#include "decode_bf16.h"
+#include "decode.h"
 #include "merge.h"
 
 using namespace tlin;
@@ -227,13 +227,21 @@ Plan plan_history(const tlin_params *p)
     return {(ntiles + tps - 1) / tps, tps};   // no partition is empty
 }
 
-// The cache-hit shape (a few query rows, long bf16 history, head dimension 128) runs in the
-// streaming kernel of decode_bf16.h when called through tlin_history_attn.
+// The cache-hit shape (a few query rows over a long history) runs in the streaming kernel of
+// decode.h when called through tlin_history_attn.
+int decode_max_rows(const tlin_params *p)
+{
+    // fp32 inputs: the matrix-core path pays for a whole 32-row tile of fp32 products whatever W is
+    // (1.39 ms over 131072 rows of 32 heads x 128 against 0.62 ms here)
+    if (p->in_dtype == TLIN_F32) return 8;
+    // bf16 at head dimension 128: three and four rows are a little faster in the two-wave matrix-core
+    // shape (0.309 against 0.323 ms over 131072 rows; both read at the rate of a plain non-temporal
+    // read stream), and so are shorter rows at any W
+    return p->D == 128 ? 2 : 0;
+}
 bool use_decode(const tlin_params *p)
 {
-    // (three and four rows are a little faster in the two-wave matrix-core shape: 0.309 against 0.323 ms
-    // over 131072 rows; both paths read at the rate a plain non-temporal read stream reaches)
-    return p->in_dtype == TLIN_BF16 && p->D == 128 && p->W <= 2 && p->N >= 1024;
+    return p->W <= decode_max_rows(p) && p->N >= 1024;
 }
 
 // One workgroup per partition; four per compute unit (they are small: four waves; more partitions
@@ -458,12 +466,26 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
     return causal ? launch_f32<64, true>(a, s, grid, st) : launch_f32<64, false>(a, s, grid, st);
 }
 
+template <typename T, int DK, bool PAD>
+const void *decode_kernel_for(int W)
+{
+    return W == 1 ? (const void *)decode_kernel<T, DK, 1, PAD> : W == 2 ? (const void *)decode_kernel<T, DK, 2, PAD>
+         : W <= 4 ? (const void *)decode_kernel<T, DK, 4, PAD> : (const void *)decode_kernel<T, DK, 8, PAD>;
+}
+const void *decode_kernel_f32(int W, int D)
+{
+    if (dpad(D) == 128) return D == 128 ? decode_kernel_for<float, 128, false>(W) : decode_kernel_for<float, 128, true>(W);
+    return D == 64 ? decode_kernel_for<float, 64, false>(W) : decode_kernel_for<float, 64, true>(W);
+}
+
 tlin_status launch_decode(const tlin_params *p, const AttnArgs &a, hipStream_t st)
 {
     const int64_t grid64 = (int64_t)p->B * p->H * a.nsplit;
-    if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
+    if (grid64 > 0x7fffffff || p->W > decode_max_rows(p)) return TLIN_ERR_INVALID_ARG;
     LaunchTimer timer(KC_HISTORY, st);
-    const void *kernel = p->W == 1 ? (const void *)decode_bf16_kernel<1> : (const void *)decode_bf16_kernel<2>;
+    const void *kernel = p->in_dtype == TLIN_F32 ? decode_kernel_f32(p->W, p->D)
+                       : p->W == 1             ? (const void *)decode_kernel<__bf16, 128, 1, false>
+                                               : (const void *)decode_kernel<__bf16, 128, 2, false>;
     return launch_kernel(kernel, dim3((unsigned)grid64), dim3(256), 0, st, a);
 }
 

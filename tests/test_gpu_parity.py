@@ -124,6 +124,39 @@ def test_streaming_decode_kernel_ragged_every_row(W, N):
     assert_close(o32, ro, w.dtype, f"{w.name} f32 out")
 
 
+@pytest.mark.parametrize("dtype,D", [(ti.BF16, 64), (ti.F32, 128), (ti.F32, 64), (ti.BF16, 36), (ti.BF16, 100),
+                                     (ti.F32, 36), (ti.F32, 100), (ti.BF16, 8), (ti.F32, 12)])
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("N", [1025, 1039, 4097, 20011])
+def test_cache_hit_shapes_dtypes_and_head_dimensions(dtype, D, W, N):
+    """Few query rows over histories of 1024 rows and more, for fp32 inputs (the streaming kernel
+    with fp32 arithmetic, up to eight rows) and for every kind of head dimension the library takes
+    (native sizes and sizes in between, with NaNs in the rows' padding); automatic and forced
+    partition counts."""
+    w = ti.Workload(f"stream_decode_{dtype}_{D}_{W}_{N}", 2, 3, D, N, W, dtype, 1.0, 70701 + 131 * D + 31 * W + N)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = {k: padded(v, w.dtype) for k, v in host.items()}
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    for s in (0, 1, 5):
+        o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, num_splits=s, return_lse=True)
+        assert o.shape[-1] == D
+        assert_close(o, ro, w.dtype, f"{w.name} splits {s}")
+        np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+
+
+@pytest.mark.parametrize("dtype,D", [(ti.F32, 128), (ti.BF16, 64), (ti.BF16, 36)])
+def test_streaming_decode_kernel_full_size_other_shapes(dtype, D):
+    """One query row over 131072 history rows of 32 heads, fp32 inputs and smaller head dimensions:
+    the launch configuration the bench times for these shapes."""
+    w = ti.Workload(f"stream_decode_full_{dtype}_{D}", 1, 32, D, 131072, 1, dtype, 1.0, 80801 + D + dtype)
+    host = ti.make(w, which=("Q", "Kh", "Vh"))
+    dev = {k: padded(v, w.dtype) for k, v in host.items()}
+    o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, return_lse=True)
+    ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
+    assert_close(o, ro, w.dtype, w.name)
+    np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+
+
 def test_streaming_decode_kernel_peaky_keys_and_strided_layout():
     """Keys of very different sizes (one row in a hundred eight times larger: the reference point
     of the online softmax moves late and far), on an interleaved-head layout."""
