@@ -55,7 +55,8 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 // The work of one workgroup; `bid` of `nblocks` is its index among the blocks of this problem set.
 // PAD: the tensors' head dimension a.D is smaller than the kernel's D.
-template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false, bool PAD = false>
+// REMAP: bid is a hardware block index (mapped to a logical one here); otherwise it is the logical index.
+template <int D, int NW, int QB, bool CAUSAL, int NSTAGE, bool RESIDENT = false, bool PAD = false, bool REMAP = true>
 __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int nblocks)
 {
     static_assert(!(RESIDENT && CAUSAL), "the resident variant is for unmasked attention");
@@ -80,7 +81,7 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
 
-    const int L = xcd_remap(bid, nblocks);
+    const int L = REMAP ? xcd_remap(bid, nblocks) : bid;
     const int qstep = RESIDENT ? a.q_groups : a.nqb;   // workgroups along the query axis of one head
     const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, qstep);
     if (pr.skip) return;                               // uniform over the workgroup
@@ -513,12 +514,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NSTAGE 
 void attn_bf16_pair_kernel(const PairArgs f)
 {
     static_assert(!NT || use_pipe_body<D, NW, 1, false, NSTAGE, false>(), "only the pipelined body has a non-temporal variant");
+    // logical index of the window block this workgroup computes, or -1
+    int win_block = (int)blockIdx.x < f.n_hist_blocks ? -1 : xcd_remap(blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
     if ((int)blockIdx.x < f.n_hist_blocks) {
-        if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) attn_bf16_pipe_body<D, NW, PAD, NT>(f.hist, blockIdx.x, f.n_hist_blocks);
-        else attn_bf16_body<D, NW, 1, false, NSTAGE, false, PAD>(f.hist, blockIdx.x, f.n_hist_blocks);
-    } else {
-        attn_bf16_body<D, NW, 1, true, NSTAGE, false, PAD>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
+        if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) {
+            attn_bf16_pipe_body<D, NW, PAD, NT>(f.hist, blockIdx.x, f.n_hist_blocks);
+            if (f.hist.fuse_window) {
+                // the workgroup of partition 0 goes on to the window's causal block of the same rows
+                // (causal blocks are numbered from the last query block down)
+                const Problem pr = decode_problem<NW * 32, 64, false>(f.hist, xcd_remap(blockIdx.x, f.n_hist_blocks), f.hist.nqb);
+                if (pr.split == 0) {
+                    win_block = pr.bh * f.win.nqb + (f.win.nqb - 1 - pr.qb);
+                    __syncthreads();      // every wave is done with the history tiles in LDS
+                }
+            }
+        } else {
+            attn_bf16_body<D, NW, 1, false, NSTAGE, false, PAD>(f.hist, blockIdx.x, f.n_hist_blocks);
+        }
     }
+    if (win_block >= 0) attn_bf16_body<D, NW, 1, true, NSTAGE, false, PAD, false>(f.win, win_block, 0);
 }
 
 }  // namespace tlin

@@ -88,8 +88,8 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
     const int b = bh / a.H, hd = bh % a.H;
     const int Wq = pr.W, NK = pr.NK;
 
-    const int t0 = CAUSAL ? 0 : split * pr.tps;
-    const int t1 = CAUSAL ? (min(NK, qb * BM + BM) + BN - 1) / BN : min(t0 + pr.tps, (NK + BN - 1) / BN);
+    int t0 = 0, t1 = (min(NK, qb * BM + BM) + BN - 1) / BN;
+    if (!CAUSAL) partition_tiles<BM, BN>(a, pr, t0, t1);
     const int nt = t1 - t0;                            // tiles of this partition (may be <= 0 in the sliding schedule)
 
     const int64_t k_rb = a.k_sr * 2, v_rb = a.v_sr * 2;

@@ -51,6 +51,10 @@ struct AttnArgs {
     int32_t out_bf16;
     int32_t direct;
     int32_t stream_once;        // host's choice: K/V rows are read by one workgroup only and exceed the caches
+    // Layer call, history launch arguments: the workgroup of partition 0 of every (head, query block)
+    // also computes the window's causal block of the same rows, and the partitions are cut so that it
+    // gets fewer key tiles by that block's cost (see partition_tiles).
+    int32_t fuse_window;
 };
 
 struct MergeArgs {
@@ -100,6 +104,16 @@ struct Problem {
     bool skip;        // nothing to do (rows past a short last chunk, or an empty history)
 };
 
+// Cost of the window's causal block of query block qb, in key tiles of the pipelined history body:
+// its tiles up to the diagonal (the unpipelined causal body takes about 5/4 of a pipelined tile's
+// time) plus loading Q and writing the partial once more.  Host and device must agree on it.
+__host__ __device__ constexpr int window_block_cost(int W, int qb, int BM, int BN)
+{
+    const int rows = (qb + 1) * BM < W ? (qb + 1) * BM : W;
+    const int wt = (rows + BN - 1) / BN;
+    return wt + wt / 4 + 2;
+}
+
 // Decode the logical block index.  BM: query rows per workgroup, BN: keys per tile.
 template <int BM, int BN, bool CAUSAL>
 __device__ __forceinline__ Problem decode_problem(const AttnArgs &a, int L, int qstep)
@@ -139,6 +153,26 @@ __device__ __forceinline__ Problem decode_problem(const AttnArgs &a, int L, int 
     }
     p.skip = p.qb * BM >= p.W || p.NK == 0;
     return p;
+}
+
+// Key tiles [t0, t1) of an unmasked partition.  Plain: partition s takes tiles s * tps ... of the
+// ceil(NK / BN).  With a.fuse_window the same tiles are cut so that partition 0, whose workgroup
+// goes on to the window block, is shorter by that block's cost and no workgroup ends later than the rest.
+template <int BM, int BN>
+__device__ __forceinline__ void partition_tiles(const AttnArgs &a, const Problem &pr, int &t0, int &t1)
+{
+    const int ntiles = (pr.NK + BN - 1) / BN;
+    if (!a.fuse_window) {
+        t0 = pr.split * pr.tps;
+        t1 = min(t0 + pr.tps, ntiles);
+        return;
+    }
+    // the cost of the head's last (longest) window block for every query block: the workgroups of one
+    // head then cut their partitions at the same tiles and keep sharing them through the XCD's L2
+    const int cost = window_block_cost(a.W, a.nqb - 1, BM, BN);
+    const int tps = (ntiles + cost + a.nsplit - 1) / a.nsplit;
+    t0 = max(pr.split * tps - cost, 0);
+    t1 = min((pr.split + 1) * tps - cost, ntiles);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

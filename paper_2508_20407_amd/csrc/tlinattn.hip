@@ -565,6 +565,21 @@ tlin_status launch_pair_kernel(const PairArgs &f, hipStream_t st)
     auto kernel = attn_bf16_pair_kernel<D, NW, NSTAGE, PAD, NT>;
     static std::atomic<uint64_t> lds_allowed{0};
     if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
+    if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) {
+        // Window blocks launched behind the history blocks run when the compute units are already
+        // taken, as a tail of their own (3 % of the largest fixed workloads' kernel time).  Where the
+        // partitions are long enough to absorb it, partition 0's workgroup computes the window block
+        // too and gets that much less history (partition_tiles): every partition stays non-empty when
+        // the tiles number at least nsplit^2 and a partition is at least four such blocks long.
+        const int tiles = (f.hist.NK + 63) / 64, ns = f.hist.nsplit;
+        const int cost = window_block_cost(f.hist.W, f.hist.nqb - 1, NW * 32, 64);
+        if (f.hist.nchunks == 0 && ns >= 2 && tiles >= ns * ns && tiles / ns >= 4 * cost) {
+            PairArgs g = f;
+            g.hist.fuse_window = 1;
+            g.n_win_blocks = 0;
+            return launch_kernel((const void *)kernel, dim3(g.n_hist_blocks), dim3(NW * 64), lds_bytes, st, g);
+        }
+    }
     return launch_kernel((const void *)kernel, dim3(f.n_hist_blocks + f.n_win_blocks), dim3(NW * 64), lds_bytes, st, f);
 }
 

@@ -51,7 +51,11 @@ def assert_close(g, r, dtype: int, what: str = "", lse: bool = False, f32_rel: f
     assert np.isfinite(g).all(), f"{what}: non-finite output"
     if dtype == ti.F32:
         e = rel_err_f32(g, r)
-        assert e <= f32_rel, f"{what}: fp32 relative error {e:.3e} > {f32_rel}"
+        big = np.abs(r) > np.sqrt(np.mean(r * r))
+        plain = float(np.max(np.abs(g - r)[big] / np.abs(r[big]))) if big.any() else 0.0
+        assert e <= f32_rel, (f"{what}: fp32 relative error {e:.3e} > {f32_rel} (denominator floored at the rms; "
+                              f"unfloored over |r| > rms: {plain:.3e})")
+        assert plain <= f32_rel, f"{what}: fp32 relative error over |r| > rms {plain:.3e} > {f32_rel}"
     else:
         d = np.abs(g - r)
         assert d.max() <= BF16_MAX_ABS, f"{what}: bf16 max abs error {d.max():.3e} > {BF16_MAX_ABS}"
