@@ -89,7 +89,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
     const int Wq = pr.W, NK = pr.NK;
 
     int t0 = 0, t1 = (min(NK, qb * BM + BM) + BN - 1) / BN;
-    if (!CAUSAL) partition_tiles<BM, BN>(a, pr, t0, t1);
+    if (!CAUSAL) partition_tiles<BM, BN, 5>(a, pr, t0, t1);
     const int nt = t1 - t0;                            // tiles of this partition (may be <= 0 in the sliding schedule)
 
     const int64_t k_rb = a.k_sr * 2, v_rb = a.v_sr * 2;

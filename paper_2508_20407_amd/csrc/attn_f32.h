@@ -35,7 +35,8 @@ struct SwzF32 {
 };
 
 // The work of one workgroup; `bid` of `nblocks` is its index among the blocks of this problem set.
-template <int D, int NW, bool CAUSAL>
+// REMAP: bid is a hardware block index (mapped to a logical one here); otherwise it is the logical index.
+template <int D, int NW, bool CAUSAL, bool REMAP = true>
 __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nblocks)
 {
     constexpr int BN = 32;                 // keys per tile
@@ -60,21 +61,15 @@ __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nb
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31, h = lane >> 5;
 
-    const int L = xcd_remap(bid, nblocks);
+    const int L = REMAP ? xcd_remap(bid, nblocks) : bid;
     const Problem pr = decode_problem<BM, BN, CAUSAL>(a, L, a.nqb);
     if (pr.skip) return;                   // uniform over the workgroup
     const int qb = pr.qb, split = pr.split, bh = pr.bh;
     const int b = bh / a.H, hd = bh % a.H;
     const int Wq = pr.W, NK = pr.NK;       // query and key rows of this problem
 
-    int t0, t1;
-    if (CAUSAL) {
-        t0 = 0;
-        t1 = (min(NK, qb * BM + BM) + BN - 1) / BN;
-    } else {
-        t0 = split * pr.tps;
-        t1 = min(t0 + pr.tps, (NK + BN - 1) / BN);
-    }
+    int t0 = 0, t1 = (min(NK, qb * BM + BM) + BN - 1) / BN;
+    if (!CAUSAL) partition_tiles<BM, BN, 4>(a, pr, t0, t1);
 
     const int64_t k_rb = a.k_sr * 4, v_rb = a.v_sr * 4;
     const float *Qg = (const float *)a.Q + (int64_t)b * a.q_sb + (int64_t)hd * a.q_sh + pr.qrow_off * a.q_sr;
@@ -303,8 +298,21 @@ __global__ __launch_bounds__(NW * 64) void attn_f32_kernel(const AttnArgs a)
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_f32_pair_kernel(const PairArgs f)
 {
-    if ((int)blockIdx.x < f.n_hist_blocks) attn_f32_body<D, NW, false>(f.hist, blockIdx.x, f.n_hist_blocks);
-    else attn_f32_body<D, NW, true>(f.win, blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
+    // logical index of the window block this workgroup computes, or -1
+    int win_block = (int)blockIdx.x < f.n_hist_blocks ? -1 : xcd_remap(blockIdx.x - f.n_hist_blocks, f.n_win_blocks);
+    if ((int)blockIdx.x < f.n_hist_blocks) {
+        attn_f32_body<D, NW, false>(f.hist, blockIdx.x, f.n_hist_blocks);
+        if (f.hist.fuse_window) {
+            // the workgroup of partition 0 goes on to the window's causal block of the same rows
+            // (causal blocks are numbered from the last query block down)
+            const Problem pr = decode_problem<NW * 32, 32, false>(f.hist, xcd_remap(blockIdx.x, f.n_hist_blocks), f.hist.nqb);
+            if (pr.split == 0) {
+                win_block = pr.bh * f.win.nqb + (f.win.nqb - 1 - pr.qb);
+                __syncthreads();      // every wave is done with the history tiles in LDS
+            }
+        }
+    }
+    if (win_block >= 0) attn_f32_body<D, NW, true, false>(f.win, win_block, 0);
 }
 
 }  // namespace tlin

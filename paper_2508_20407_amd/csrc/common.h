@@ -104,14 +104,15 @@ struct Problem {
     bool skip;        // nothing to do (rows past a short last chunk, or an empty history)
 };
 
-// Cost of the window's causal block of query block qb, in key tiles of the pipelined history body:
-// its tiles up to the diagonal (the unpipelined causal body takes about 5/4 of a pipelined tile's
-// time) plus loading Q and writing the partial once more.  Host and device must agree on it.
-__host__ __device__ constexpr int window_block_cost(int W, int qb, int BM, int BN)
+// Cost of the window's causal block of query block qb, in key tiles of the history body: its tiles
+// up to the diagonal, each taking QUARTERS / 4 of a history tile's time (bf16: the unpipelined
+// causal body takes about 5/4 of a pipelined tile; fp32: the same body, 4/4), plus loading Q and
+// writing the partial once more.  Host and device must agree on it.
+__host__ __device__ constexpr int window_block_cost(int W, int qb, int BM, int BN, int QUARTERS)
 {
     const int rows = (qb + 1) * BM < W ? (qb + 1) * BM : W;
     const int wt = (rows + BN - 1) / BN;
-    return wt + wt / 4 + 2;
+    return wt * QUARTERS / 4 + 2;
 }
 
 // Decode the logical block index.  BM: query rows per workgroup, BN: keys per tile.
@@ -158,7 +159,7 @@ __device__ __forceinline__ Problem decode_problem(const AttnArgs &a, int L, int 
 // Key tiles [t0, t1) of an unmasked partition.  Plain: partition s takes tiles s * tps ... of the
 // ceil(NK / BN).  With a.fuse_window the same tiles are cut so that partition 0, whose workgroup
 // goes on to the window block, is shorter by that block's cost and no workgroup ends later than the rest.
-template <int BM, int BN>
+template <int BM, int BN, int QUARTERS>
 __device__ __forceinline__ void partition_tiles(const AttnArgs &a, const Problem &pr, int &t0, int &t1)
 {
     const int ntiles = (pr.NK + BN - 1) / BN;
@@ -169,7 +170,7 @@ __device__ __forceinline__ void partition_tiles(const AttnArgs &a, const Problem
     }
     // the cost of the head's last (longest) window block for every query block: the workgroups of one
     // head then cut their partitions at the same tiles and keep sharing them through the XCD's L2
-    const int cost = window_block_cost(a.W, a.nqb - 1, BM, BN);
+    const int cost = window_block_cost(a.W, a.nqb - 1, BM, BN, QUARTERS);
     const int tps = (ntiles + cost + a.nsplit - 1) / a.nsplit;
     t0 = max(pr.split * tps - cost, 0);
     t1 = min((pr.split + 1) * tps - cost, ntiles);

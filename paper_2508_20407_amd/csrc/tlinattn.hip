@@ -397,14 +397,32 @@ tlin_status launch_f32(const AttnArgs &a, Shape s, int grid, hipStream_t st)
     return launch_kernel((const void *)attn_f32_kernel<D, 2, CAUSAL>, dim3(grid), dim3(128), lds_bytes / 2, st, a);
 }
 
+// Window blocks launched behind the history blocks run when the compute units are already taken, as
+// a tail of their own (1.5 to 5 % of the larger workloads' kernel time).  Where the partitions are
+// long enough to absorb it, partition 0's workgroup computes the window block too and gets that
+// much less history (partition_tiles): every partition stays non-empty when the tiles number at
+// least nsplit^2 and a partition is at least four such blocks long.  BM, BN, quarters: the kernel's
+// query rows per workgroup, keys per tile and cost ratio (window_block_cost).
+bool fuses_window(const PairArgs &f, int BM, int BN, int quarters)
+{
+    const int tiles = (f.hist.NK + BN - 1) / BN, ns = f.hist.nsplit;
+    const int cost = window_block_cost(f.hist.W, f.hist.nqb - 1, BM, BN, quarters);
+    return f.hist.nchunks == 0 && f.n_win_blocks > 0 && ns >= 2 && tiles >= ns * ns && tiles / ns >= 4 * cost;
+}
+
 template <int D>
 tlin_status launch_f32_pair(const PairArgs &f, Shape s, hipStream_t st)
 {
     constexpr int lds_bytes = 2 * 2 * 32 * D * 4;
-    const dim3 grid(f.n_hist_blocks + f.n_win_blocks);
-    if (s.nw == 8) return launch_kernel((const void *)attn_f32_pair_kernel<D, 8>, grid, dim3(512), lds_bytes, st, f);
-    if (s.nw == 4) return launch_kernel((const void *)attn_f32_pair_kernel<D, 4>, grid, dim3(256), lds_bytes, st, f);
-    return launch_kernel((const void *)attn_f32_pair_kernel<D, 2>, grid, dim3(128), lds_bytes / 2, st, f);
+    PairArgs g = f;
+    if (fuses_window(f, s.nw * 32, 32, 4)) {
+        g.hist.fuse_window = 1;
+        g.n_win_blocks = 0;
+    }
+    const dim3 grid(g.n_hist_blocks + g.n_win_blocks);
+    if (s.nw == 8) return launch_kernel((const void *)attn_f32_pair_kernel<D, 8>, grid, dim3(512), lds_bytes, st, g);
+    if (s.nw == 4) return launch_kernel((const void *)attn_f32_pair_kernel<D, 4>, grid, dim3(256), lds_bytes, st, g);
+    return launch_kernel((const void *)attn_f32_pair_kernel<D, 2>, grid, dim3(128), lds_bytes / 2, st, g);
 }
 
 // Key tiles the resident variant keeps in LDS (128 KB of keys and values).
@@ -566,14 +584,7 @@ tlin_status launch_pair_kernel(const PairArgs &f, hipStream_t st)
     static std::atomic<uint64_t> lds_allowed{0};
     if (allow_lds((const void *)kernel, lds_bytes, lds_allowed) != TLIN_OK) return TLIN_ERR_HIP;
     if constexpr (use_pipe_body<D, NW, 1, false, NSTAGE, false>()) {
-        // Window blocks launched behind the history blocks run when the compute units are already
-        // taken, as a tail of their own (3 % of the largest fixed workloads' kernel time).  Where the
-        // partitions are long enough to absorb it, partition 0's workgroup computes the window block
-        // too and gets that much less history (partition_tiles): every partition stays non-empty when
-        // the tiles number at least nsplit^2 and a partition is at least four such blocks long.
-        const int tiles = (f.hist.NK + 63) / 64, ns = f.hist.nsplit;
-        const int cost = window_block_cost(f.hist.W, f.hist.nqb - 1, NW * 32, 64);
-        if (f.hist.nchunks == 0 && ns >= 2 && tiles >= ns * ns && tiles / ns >= 4 * cost) {
+        if (fuses_window(f, NW * 32, 64, 5)) {
             PairArgs g = f;
             g.hist.fuse_window = 1;
             g.n_win_blocks = 0;

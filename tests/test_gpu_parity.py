@@ -295,15 +295,16 @@ def test_slide_full_size_stratified_rows():
     run_slide(w, 512, rows=np.unique(rows).astype(np.int32))
 
 
+@pytest.mark.parametrize("dtype", [ti.BF16, ti.F32])
 @pytest.mark.parametrize("D", [128, 64, 36])
 @pytest.mark.parametrize("W", [40, 128, 300, 512])
 @pytest.mark.parametrize("N,splits", [(20000, 2), (20000, 5), (40001, 0), (9000, 3)])
-def test_layer_call_whose_window_blocks_ride_on_partition_0(D, W, N, splits):
+def test_layer_call_whose_window_blocks_ride_on_partition_0(dtype, D, W, N, splits):
     """Layer calls with partitions long enough that no window block is launched: the workgroup of
     partition 0 also computes the window's causal block, and every partition's bounds are shifted
     by that block's cost.  Every row, both combine modes, forced and automatic partition counts,
     one and two query blocks per head, a ragged last key tile."""
-    w = ti.Workload(f"fused_{D}_{W}_{N}_{splits}", 1, 2, D, N, W, ti.BF16, 1.0, 515151 + D + 7 * W + N + splits)
+    w = ti.Workload(f"fused_{dtype}_{D}_{W}_{N}_{splits}", 1, 2, D, N, W, dtype, 1.0, 515151 + D + 7 * W + N + splits + dtype)
     host = ti.make(w)
     dev = {k: padded(v, w.dtype) for k, v in host.items()}
     for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
