@@ -62,7 +62,7 @@ struct Strides { int64_t b, h, r; };
 // Kernel shape chosen for a bf16 problem: NW waves, QB query blocks of 32 rows per wave.
 struct Shape { int nw, qb; int bm() const { return nw * qb * 32; } };
 
-Shape bf16_shape(int W)
+Shape wave_shape(int W)
 {
     if (W > 128) return {8, 1};
     if (W > 64) return {4, 1};
@@ -76,7 +76,17 @@ int dpad(int D) { return D <= 64 ? 64 : 128; }
 // Keys per tile: 32 KB of K and V per tile in both kernels.  Query rows per workgroup: the same
 // shapes for both input types.
 int key_tile(int in_dtype, int) { return in_dtype == TLIN_F32 ? 32 : 64; }
-int query_block(int, int W) { return bf16_shape(W).bm(); }
+// bf16 at head dimension 64 and below stays with four waves for long windows too: its pipelined body
+// takes 153 registers, so three waves fit a SIMD, which is three four-wave workgroups per compute
+// unit but only one of eight waves (12 heads x 36, 256 window rows over 131072 / 999754 history
+// rows: 0.135 / 0.911 ms per step against 0.148 / 0.940 ms with eight-wave workgroups).
+Shape kernel_shape(int in_dtype, int W, int D)
+{
+    const Shape s = wave_shape(W);
+    if (in_dtype == TLIN_BF16 && dpad(D) == 64 && s.nw == 8) return {4, 1};
+    return s;
+}
+int query_block(int in_dtype, int W, int D) { return kernel_shape(in_dtype, W, D).bm(); }
 
 // Workgroups the chip holds at once for a given kernel shape (LDS- and register-limited).
 int resident_wgs(int in_dtype, int W, int D)
@@ -85,7 +95,7 @@ int resident_wgs(int in_dtype, int W, int D)
         // fp32 kernel: two waves per SIMD keep the matrix cores busy (8 waves per compute unit); its
         // tile ring takes 64 KB of the 160 KB of LDS at D = 128 and 32 KB at D = 64 (half of that in
         // the two-wave shape)
-        const int nw = bf16_shape(W).nw;
+        const int nw = wave_shape(W).nw;
         const int by_waves = 8 / nw, by_lds = (dpad(D) == 128 ? 2 : 4) * (nw == 2 ? 2 : 1);
         return kNumCU * (by_waves < by_lds ? by_waves : by_lds);
     }
@@ -93,7 +103,7 @@ int resident_wgs(int in_dtype, int W, int D)
     // compute unit (measured best for few heads); 128: an eight-wave workgroup fills a compute unit
     // alone (registers), two of the smaller ones share it (two-tile LDS ring of 64 KB each)
     if (dpad(D) == 64) return kNumCU * 3;
-    return kNumCU * (bf16_shape(W).nw == 8 ? 1 : 2);
+    return kNumCU * (wave_shape(W).nw == 8 ? 1 : 2);
 }
 
 // ---- measurement aid: per-kernel timing with HIP events on the launch stream
@@ -211,7 +221,7 @@ Plan plan_history(const tlin_params *p)
     } else {
         // Enough workgroups to occupy every compute unit, but at least 8 tiles per partition: the
         // merge reads every partial, and with short partitions it would cost more than they save.
-        const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W) - 1) / query_block(p->in_dtype, p->W));
+        const int64_t base = (int64_t)p->B * p->H * ((p->W + query_block(p->in_dtype, p->W, p->D) - 1) / query_block(p->in_dtype, p->W, p->D));
         const int64_t target = resident_wgs(p->in_dtype, p->W, p->D);
         want = (int)((target + base - 1) / base);
         // (a handful of (head, query block) items cannot fill the chip anyway: there the partials
@@ -273,7 +283,7 @@ SlidePlan plan_slide(const tlin_params *p)
 {
     const int nchunks = (p->N + p->W - 1) / p->W;
     const int bn = key_tile(p->in_dtype, dpad(p->D));
-    const int qblk = query_block(p->in_dtype, p->W);
+    const int qblk = query_block(p->in_dtype, p->W, p->D);
     const int nqb = (p->W + qblk - 1) / qblk;
     int want;
     if (p->num_splits > 0) {
@@ -433,9 +443,9 @@ int resident_tiles(int D) { return D == 128 ? 4 : 8; }
 bool use_resident(const tlin_params *p, bool causal, const AttnArgs &a)
 {
     if (causal || p->in_dtype != TLIN_BF16 || !a.direct || a.nsplit != 1) return false;
-    if (bf16_shape(p->W).nw != 8) return false;
+    if (p->W <= 128) return false;
     const int ntiles = (a.NK + 63) / 64;
-    const int64_t blocks = (int64_t)p->B * p->H * a.nqb;
+    const int64_t blocks = (int64_t)p->B * p->H * ((p->W + 255) / 256);      // the resident kernels are eight-wave ones
     return ntiles <= resident_tiles(dpad(p->D)) && blocks >= 4 * (int64_t)kNumCU;
 }
 
@@ -452,11 +462,12 @@ bool streams_once(const tlin_params *p, const AttnArgs &a, int nqb)
 // Launch one partial-attention kernel over `nsplit` key partitions (or the causal window).
 tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream_t st)
 {
-    const int qblk = query_block(p->in_dtype, p->W);
+    const int qblk = query_block(p->in_dtype, p->W, p->D);
     a.nqb = (p->W + qblk - 1) / qblk;
     a.stream_once = !causal && streams_once(p, a, a.nqb);
     if (use_resident(p, causal, a)) {
         // one workgroup per compute unit, spread evenly over the heads
+        a.nqb = (p->W + 255) / 256;
         const int64_t bh = (int64_t)p->B * p->H;
         int64_t g = (kNumCU + bh - 1) / bh;
         if (g > a.nqb) g = a.nqb;
@@ -475,7 +486,7 @@ tlin_status launch_attn(const tlin_params *p, bool causal, AttnArgs a, hipStream
     if (grid64 > 0x7fffffff) return TLIN_ERR_INVALID_ARG;
     const int grid = (int)grid64;
     LaunchTimer timer(causal ? KC_WINDOW : KC_HISTORY, st);
-    const Shape s = bf16_shape(p->W);
+    const Shape s = kernel_shape(p->in_dtype, p->W, p->D);
     if (p->in_dtype == TLIN_BF16) {
         if (dpad(p->D) == 128) return causal ? launch_bf16<128, true>(a, s, grid, st) : launch_bf16<128, false>(a, s, grid, st);
         return causal ? launch_bf16<64, true>(a, s, grid, st) : launch_bf16<64, false>(a, s, grid, st);
@@ -613,7 +624,7 @@ tlin_status launch_pair_shape(const PairArgs &f, hipStream_t st)
 // History partials and window partial of the same rows: one launch for both problem sets.
 tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const AttnArgs &aw, hipStream_t hs)
 {
-    const int qblk = query_block(p->in_dtype, p->W);
+    const int qblk = query_block(p->in_dtype, p->W, p->D);
     const int nqb = (p->W + qblk - 1) / qblk;
     const int64_t per_set = (int64_t)p->B * p->H * nqb * (ah.nchunks ? ah.nchunks : 1);
     const int64_t nh = per_set * ah.nsplit, nw = per_set;
@@ -625,7 +636,7 @@ tlin_status launch_partials(const tlin_params *p, const AttnArgs &ah, const Attn
         f.hist.stream_once = streams_once(p, ah, nqb);
         f.n_hist_blocks = (int)nh;
         f.n_win_blocks = (int)nw;
-        const Shape s = bf16_shape(p->W);
+        const Shape s = kernel_shape(p->in_dtype, p->W, p->D);
         LaunchTimer timer(KC_HISTORY, hs);
         if (p->in_dtype == TLIN_F32) return dpad(p->D) == 128 ? launch_f32_pair<128>(f, s, hs) : launch_f32_pair<64>(f, s, hs);
         if (dpad(p->D) == 128) {
