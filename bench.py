@@ -452,10 +452,10 @@ def main():
 # sources are the ones it was measured on (csrc_sha16 below = kernel_sources_sha16() at that time);
 # otherwise `traffic` is null and `traffic_source` says why.
 MEASURED_TRAFFIC = {
-    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_988.3 * 2.0 * 1024) + int(41_600.1 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
-                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "18ca71819b616e74"},
-    "decode_bf16_N131072_W1": {"bytes": int(1_055_874.7 * 2.0 * 1024) + int(576.3 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
-                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": "18ca71819b616e74"},
+    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_966.1 * 2.0 * 1024) + int(41_600.0 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
+                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "6958dfe247894b72"},
+    "decode_bf16_N131072_W1": {"bytes": int(1_055_792.4 * 2.0 * 1024) + int(576.3 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
+                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": "6958dfe247894b72"},
 }
 
 

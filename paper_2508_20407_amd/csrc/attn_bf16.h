@@ -156,13 +156,11 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
     for (int i = 0; i < NDMA; ++i) {
         drow[i] = (wave * NDMA + i) * RPI + lane / CPR;
         // rows shorter than the kernel's D (a.D < D): chunks past the end of a row are not in
-        // memory; chunk 0 (complete, as a.D >= 8) is fetched in their place (they only meet zero
-        // columns of Q, and the output columns they produce are not stored)
-        int kc = (lane % CPR) ^ Swz<D>::k(drow[i]), vc = (lane % CPR) ^ Swz<D>::v(drow[i]);
-        if (PAD && kc >= dchunks) kc = 0;
-        if (PAD && vc >= dchunks) vc = 0;
-        koff[i] = (unsigned)(drow[i] * k_rb) + (kc << 4);
-        voff[i] = (unsigned)(drow[i] * v_rb) + (vc << 4);
+        // memory; their places in LDS are cleared instead (they only meet zero columns of Q, and the
+        // output columns they produce are not stored)
+        const int kc = (lane % CPR) ^ Swz<D>::k(drow[i]), vc = (lane % CPR) ^ Swz<D>::v(drow[i]);
+        koff[i] = (PAD && kc >= dchunks) ? kNoChunk : (unsigned)(drow[i] * k_rb) + (kc << 4);
+        voff[i] = (PAD && vc >= dchunks) ? kNoChunk : (unsigned)(drow[i] * v_rb) + (vc << 4);
     }
     auto issue = [&](int t, int stage) __attribute__((always_inline)) {
         const int key0 = t * BN;
@@ -171,8 +169,8 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs &a, int bid, int n
         // rows past the end of the tensor (ragged last tile) lie beyond the descriptor's size and
         // arrive as zeros; their scores are masked
         const int rows = min(BN, NK - key0);
-        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
-        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
+        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, (PAD || rows < BN) ? (unsigned)(rows * k_rb) : 0xffffffffu);
+        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, (PAD || rows < BN) ? (unsigned)(rows * v_rb) : 0xffffffffu);
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) {
             direct_load_1k(kd, koff[i], kdst + i * 1024);

@@ -131,25 +131,23 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
 #pragma unroll
     for (int i = 0; i < NDMA; ++i) {
         const int drow = (wave * NDMA + i) * RPI + lane / CPR;
-        int kc = (lane % CPR) ^ Swz<D>::k(drow), vc = (lane % CPR) ^ Swz<D>::v(drow);
-        if (PAD && kc >= dchunks) kc = 0;
-        if (PAD && vc >= dchunks) vc = 0;
-        koff[i] = (unsigned)(drow * k_rb) + (kc << 4);
-        voff[i] = (unsigned)(drow * v_rb) + (vc << 4);
+        const int kc = (lane % CPR) ^ Swz<D>::k(drow), vc = (lane % CPR) ^ Swz<D>::v(drow);
+        koff[i] = (PAD && kc >= dchunks) ? kNoChunk : (unsigned)(drow * k_rb) + (kc << 4);
+        voff[i] = (PAD && vc >= dchunks) ? kNoChunk : (unsigned)(drow * v_rb) + (vc << 4);
     }
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_offset(Ks) + wave * (NDMA * 1024));
     // local tile index n (tile t0 + n) into ring stage `stage`
     auto issue_k = [&](int n, int stage) __attribute__((always_inline)) {
         const int key0 = (t0 + n) * BN;
         const int rows = min(BN, NK - key0);
-        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
+        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, (PAD || rows < BN) ? (unsigned)(rows * k_rb) : 0xffffffffu);
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) direct_load_1k<NT>(kd, koff[i], lds_wave + stage * TILE_B + i * 1024);
     };
     auto issue_v = [&](int n, int stage) __attribute__((always_inline)) {
         const int key0 = (t0 + n) * BN;
         const int rows = min(BN, NK - key0);
-        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
+        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, (PAD || rows < BN) ? (unsigned)(rows * v_rb) : 0xffffffffu);
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) direct_load_1k<NT>(vd, voff[i], lds_wave + (NSTAGE + stage) * TILE_B + i * 1024);
     };
@@ -278,7 +276,7 @@ __device__ __forceinline__ void attn_bf16_pipe_body(const AttnArgs &a, int bid, 
         const int key0 = tile * BN;
         const int rows = min(BN, NK - key0);
         const int64_t rb = isk ? k_rb : v_rb;
-        const u32x4 d = tile_descriptor((isk ? Kg : Vg) + key0 * rb, rows < BN ? (unsigned)(rows * rb) : 0xffffffffu);
+        const u32x4 d = tile_descriptor((isk ? Kg : Vg) + key0 * rb, (PAD || rows < BN) ? (unsigned)(rows * rb) : 0xffffffffu);
         const int ii = isk ? i : i - NDMA;
         direct_load_1k<NT>(d, isk ? koff[ii] : voff[ii], lds_wave + ((isk ? kfree : NSTAGE + vfree)) * TILE_B + ii * 1024);
     };
@@ -537,16 +535,14 @@ __device__ __forceinline__ void attn_bf16_resident_pipe_body(const AttnArgs &a, 
         for (int t = 0; t < T1; ++t) {
             const int key0 = t * BN;
             const int rows = min(BN, NK - key0);
-            const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
-            const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
+            const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, (PAD || rows < BN) ? (unsigned)(rows * k_rb) : 0xffffffffu);
+            const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, (PAD || rows < BN) ? (unsigned)(rows * v_rb) : 0xffffffffu);
 #pragma unroll
             for (int i = 0; i < NDMA; ++i) {
                 const int drow = (wave * NDMA + i) * RPI + lane / CPR;
-                int kc = (lane % CPR) ^ Swz<D>::k(drow), vc = (lane % CPR) ^ Swz<D>::v(drow);
-                if (PAD && kc >= dchunks) kc = 0;
-                if (PAD && vc >= dchunks) vc = 0;
-                direct_load_1k(kd, (unsigned)(drow * k_rb) + (kc << 4), lds_wave + t * TILE_B + i * 1024);
-                direct_load_1k(vd, (unsigned)(drow * v_rb) + (vc << 4), lds_wave + (TMAX + t) * TILE_B + i * 1024);
+                const int kc = (lane % CPR) ^ Swz<D>::k(drow), vc = (lane % CPR) ^ Swz<D>::v(drow);
+                direct_load_1k(kd, (PAD && kc >= dchunks) ? kNoChunk : (unsigned)(drow * k_rb) + (kc << 4), lds_wave + t * TILE_B + i * 1024);
+                direct_load_1k(vd, (PAD && vc >= dchunks) ? kNoChunk : (unsigned)(drow * v_rb) + (vc << 4), lds_wave + (TMAX + t) * TILE_B + i * 1024);
             }
         }
     }

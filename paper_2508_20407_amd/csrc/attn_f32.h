@@ -22,8 +22,9 @@
 //     128-bit read cover all 64 banks; V chunk ^ 8 for rows with bit 2 set, so that the two
 //     half-waves (rows 4 apart, same columns) read different halves of the bank sweep.
 //   * Tensors with a head dimension a.D below the kernel's D: a.D is a multiple of 4, so 16-byte
-//     chunks are either whole or absent; absent chunks are replaced by chunk 0 at the load and meet
-//     zero columns of Q, and output columns from a.D on are not stored.
+//     chunks are either whole or absent; the places of absent chunks are cleared in LDS by the load
+//     (lane offsets beyond the tile descriptor's size: zeros, no memory request) and meet zero
+//     columns of Q, and output columns from a.D on are not stored.
 #pragma once
 #include "common.h"
 
@@ -97,11 +98,9 @@ __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nb
 #pragma unroll
     for (int i = 0; i < NDMA; ++i) {
         const int drow = (wave * NDMA + i) * RPI + lane / CPR;
-        int kc = (lane % CPR) ^ SwzF32::k(drow), vc = (lane % CPR) ^ SwzF32::v(drow);
-        if (kc >= dchunks) kc = 0;
-        if (vc >= dchunks) vc = 0;
-        koff[i] = (unsigned)(drow * k_rb) + (kc << 4);
-        voff[i] = (unsigned)(drow * v_rb) + (vc << 4);
+        const int kc = (lane % CPR) ^ SwzF32::k(drow), vc = (lane % CPR) ^ SwzF32::v(drow);
+        koff[i] = kc >= dchunks ? kNoChunk : (unsigned)(drow * k_rb) + (kc << 4);
+        voff[i] = vc >= dchunks ? kNoChunk : (unsigned)(drow * v_rb) + (vc << 4);
     }
     auto issue = [&](int t, int stage) __attribute__((always_inline)) {
         const int key0 = t * BN;
@@ -109,8 +108,8 @@ __device__ __forceinline__ void attn_f32_body(const AttnArgs &a, int bid, int nb
         const unsigned vdst = kdst + NSTAGE * TILE_B;
         // rows past the end of the tensor lie beyond the descriptor's size and arrive as zeros
         const int rows = min(BN, NK - key0);
-        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, rows < BN ? (unsigned)(rows * k_rb) : 0xffffffffu);
-        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, rows < BN ? (unsigned)(rows * v_rb) : 0xffffffffu);
+        const u32x4 kd = tile_descriptor(Kg + key0 * k_rb, (a.D < D || rows < BN) ? (unsigned)(rows * k_rb) : 0xffffffffu);
+        const u32x4 vd = tile_descriptor(Vg + key0 * v_rb, (a.D < D || rows < BN) ? (unsigned)(rows * v_rb) : 0xffffffffu);
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) {
             direct_load_1k(kd, koff[i], kdst + i * 1024);

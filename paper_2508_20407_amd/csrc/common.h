@@ -228,6 +228,11 @@ __device__ __forceinline__ u32x4 tile_descriptor(const char *base, unsigned byte
 // 64-row window over 262144 history rows: 5.8 -> 6.9 TB/s); for small, latency-bound problems and
 // for tiles that a second query block re-reads from L2 it costs a few per cent, so it is a choice
 // of the host per call.
+// A lane offset beyond the size of every tile descriptor: the lane's 16 bytes of LDS are cleared and
+// no memory request is made.  For the chunks that rows shorter than the kernel's head dimension do
+// not have (descriptors of such tensors always carry the tile's real size).
+constexpr unsigned kNoChunk = 0xfffffff0u;
+
 template <bool NT = false>
 __device__ __forceinline__ void direct_load_1k(u32x4 desc, unsigned byte_off, unsigned lds_base)
 {
