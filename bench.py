@@ -451,11 +451,23 @@ def main():
 # two counters are in the profile files named here).  A figure is only reported while the kernel
 # sources are the ones it was measured on (csrc_sha16 below = kernel_sources_sha16() at that time);
 # otherwise `traffic` is null and `traffic_source` says why.
+_SHA = "6958dfe247894b72"      # kernel_sources_sha16() when the counters below were read
 MEASURED_TRAFFIC = {
-    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_966.1 * 2.0 * 1024) + int(41_600.0 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
-                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": "6958dfe247894b72"},
-    "decode_bf16_N131072_W1": {"bytes": int(1_055_792.4 * 2.0 * 1024) + int(576.3 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
-                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": "6958dfe247894b72"},
+    # workload: (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024, profile file with the raw readings
+    "cfg4_bf16_N131072_W512": {"bytes": int(1_056_966.8 * 2.0 * 1024) + int(41_600.0 * 1024),   # 2.016 GiB fetched + 40.6 MiB written
+                               "profile": "profiles/attn_bf16_pair_cfg4_pmc.md", "csrc_sha16": _SHA},
+    "decode_bf16_N131072_W1": {"bytes": int(1_055_860.0 * 2.0 * 1024) + int(576.2 * 1024),      # 2.014 GiB fetched + 0.6 MiB written
+                               "profile": "profiles/decode_bf16_w1.md", "csrc_sha16": _SHA},
+    "cfg3_bf16_N32768_W256_peaky": {"bytes": int(532_236.9 * 2.0 * 1024) + int(41_600.0 * 1024),    # 1.015 GiB + 40.6 MiB
+                                    "profile": "profiles/attn_bf16_pair_cfg3_kernel_trace.md", "csrc_sha16": _SHA},
+    "restore_bf16_Q131072_K256": {"bytes": int(526_450.8 * 2.0 * 1024) + int(1_048_576.0 * 1024),    # 1.004 GiB (Q) + 1 GiB (O)
+                                  "profile": "profiles/attn_bf16_resident_restore_kernel_trace.md", "csrc_sha16": _SHA},
+    "f32_N131072_W1": {"bytes": int(2_108_624.1 * 2.0 * 1024) + int(576.3 * 1024),                  # 4.022 GiB + 0.6 MiB
+                       "profile": "profiles/decode_f32_w1.md", "csrc_sha16": _SHA},
+    "f32_N32768_W512": {"bytes": int(540_852.3 * 2.0 * 1024) + int(41_600.0 * 1024),                # 1.032 GiB + 40.6 MiB
+                        "profile": "profiles/attn_f32_pair_N32768_W512.md", "csrc_sha16": _SHA},
+    "paper_bf16_H12_D36_N999754_W256": {"bytes": int(955_056.1 * 2.0 * 1024) + int(26_136.0 * 1024),   # 1.822 GiB + 25.5 MiB
+                                        "profile": "profiles/attn_bf16_pair_paper_hd36_N999754.md", "csrc_sha16": _SHA},
 }
 
 
