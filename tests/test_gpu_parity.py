@@ -314,6 +314,45 @@ def test_layer_call_whose_window_blocks_ride_on_partition_0(dtype, D, W, N, spli
         assert_close(o, ro, w.dtype, f"{w.name} mode {mode}")
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes_through_every_entry_point(seed):
+    """Eighty seeded random problems per seed: input type, head dimension (native sizes and sizes in
+    between, NaN padding), batch and heads, history length 1 ... 400000 and window 1 ... 600
+    (log-uniform), automatic and forced partition counts, a quarter of the bf16 ones with peaky keys;
+    history, window and both layer modes against the oracle (all rows, or a sample when the problem
+    is large)."""
+    import math
+    import random
+    rng = random.Random(424200 + seed)
+    for case in range(80):
+        dtype = rng.choice([ti.BF16, ti.BF16, ti.F32])
+        D = rng.choice([128, 128, 64, 64, 36, 8, 12, 40, 48, 96, 100, 120, 16, 32])
+        B, H = rng.choice([1, 1, 2]), rng.choice([1, 2, 3, 5])
+        N = int(round(math.exp(rng.uniform(0, math.log(400000)))))
+        W = int(round(math.exp(rng.uniform(0, math.log(600)))))
+        splits = rng.choice([0, 0, 0, 1, 2, 3, 5, 17])
+        peaky = dtype == ti.BF16 and rng.random() < 0.25
+        w = ti.Workload(f"random{seed}_{case}", B, H, D, N, W, dtype, 1.0, 9000000 + 1000 * seed + case,
+                        peaky_mod=50 if peaky else 0, peaky_factor=6.0 if peaky else 1.0)
+        what = f"{w.name}: dtype {dtype} B{B} H{H} D{D} N{N} W{W} splits {splits} peaky {peaky}"
+        host = ti.make(w)
+        dev = {k: padded(v, w.dtype) for k, v in host.items()}
+        rows = None if W * N <= 3_000_000 else sample_rows(W, max(4, 3_000_000 // N), seed=case)
+        sel = (lambda t: t) if rows is None else (lambda t: t[:, :, torch.from_numpy(rows).long().cuda()])
+        o, lse = tl.tlin_history_attn(dev["Q"], dev["Kh"], dev["Vh"], scale=w.scale, num_splits=splits, return_lse=True)
+        ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale, rows)
+        assert_close(sel(o), ro, w.dtype, f"{what} history")
+        np.testing.assert_allclose(to_host64(sel(lse.unsqueeze(-1)))[..., 0], rl, rtol=1e-6, atol=lse_atol(w.dtype, rl), err_msg=what)
+        o = tl.tlin_window_causal_attn(dev["Q"], dev["Kw"], dev["Vw"], scale=w.scale)
+        ro, _ = oracle.window_causal(host["Q"], host["Kw"], host["Vw"], w.dtype, w.scale, rows)
+        assert_close(sel(o), ro, w.dtype, f"{what} window")
+        for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+            o = tl.tlin_layer_attn(dev["Q"], dev["Kh"], dev["Vh"], dev["Kw"], dev["Vw"], combine=mode, scale=w.scale,
+                                   num_splits=splits)
+            ro = oracle.layer(host["Q"], host["Kh"], host["Vh"], host["Kw"], host["Vw"], w.dtype, w.scale, omode, rows)
+            assert_close(sel(o), ro, w.dtype, f"{what} layer mode {mode}")
+
+
 # ---------------------------------------------------------------- head dimensions between the native sizes
 def padded(a: np.ndarray, dtype: int) -> torch.Tensor:
     """Device tensor whose rows are padded to whole 16-byte pieces; the padding holds NaNs (it
