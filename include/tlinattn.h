@@ -36,10 +36,12 @@
  *     any HIP call, so it behaves the same on a machine without a GPU.
  *   - Each (b, h) is an independent attention problem; there is no positional term, bias,
  *     dropout or key/value head sharing.  Non-finite inputs give unspecified outputs.
- *   - Results are exact softmax attention up to rounding: bf16 inputs are multiplied on the
- *     matrix cores with fp32 accumulation, softmax weights are rounded to bf16 before the
- *     second product; fp32 inputs use fp32 arithmetic throughout (fp32 matrix instructions,
- *     nothing is rounded below fp32).
+ *   - Results are exact softmax attention up to rounding: bf16 inputs are multiplied with fp32
+ *     accumulation (on the matrix cores; with the dot-product instructions of the vector unit
+ *     where one or two query rows meet a long history), softmax weights are rounded to bf16
+ *     before the second product; fp32 inputs use fp32 arithmetic throughout (fp32 matrix
+ *     instructions, or fp32 multiply-adds of the vector unit for up to eight query rows over a
+ *     long history; nothing is rounded below fp32).
  *   - Accuracy envelope.  bf16 inputs: |O - exact| <= 2e-2 (mean <= 5e-3) for inputs of unit
  *     scale.  fp32 inputs: a logit is an fp32 sum of D products and carries an absolute error of
  *     a few 2^-24 of its own size, which the exponential turns into the same RELATIVE error of
