@@ -175,7 +175,8 @@ def test_streaming_decode_kernel_peaky_keys_and_strided_layout():
 
 def test_decode_shape_at_the_papers_maximum_length():
     """Cache-hit step over 2^20 history rows (Section 6.4 runs sequences beyond one million
-    tokens), 32 heads of dimension 128: 16 GiB of keys and values, every output row compared."""
+    tokens), 32 heads of dimension 128: 16 GiB of keys and values, every output row compared; then
+    the layer call of a 512-row window over the same history."""
     w = ti.decode_point(1048576, 1)
     host = ti.make(w, which=("Q", "Kh", "Vh"))
     dev = upload(host, w.dtype)
@@ -183,6 +184,17 @@ def test_decode_shape_at_the_papers_maximum_length():
     ro, rl = oracle.history(host["Q"], host["Kh"], host["Vh"], w.dtype, w.scale)
     assert_close(o, ro, w.dtype, w.name)
     np.testing.assert_allclose(to_host64(lse), rl, rtol=1e-6, atol=lse_atol(w.dtype, rl))
+    # the cache-miss layer call of a 512-row window over the same history (partitions of 4096 key
+    # tiles; the window blocks ride on partition 0), first and last row of every 32-row block
+    w2 = ti.Workload("layer_N1048576_W512", w.B, w.H, w.D, w.N, 512, w.dtype, 1.0, w.seed + 1)
+    win = ti.make(w2, which=("Q", "Kw", "Vw"))
+    dwin = upload(win, w.dtype)
+    rows = stratified_rows(512)
+    idx = torch.from_numpy(rows).long().cuda()
+    for mode, omode in ((tl.TLIN_COMBINE_SUM, oracle.SUM), (tl.TLIN_COMBINE_JOINT, oracle.JOINT)):
+        o = tl.tlin_layer_attn(dwin["Q"], dev["Kh"], dev["Vh"], dwin["Kw"], dwin["Vw"], combine=mode, scale=w.scale)
+        ro = oracle.layer(win["Q"], host["Kh"], host["Vh"], win["Kw"], win["Vw"], w.dtype, w.scale, omode, rows)
+        assert_close(o[:, :, idx], ro, w.dtype, f"{w2.name} mode {mode}")
 
 
 @pytest.mark.parametrize("dtype", [ti.F32, ti.BF16])
